@@ -1,0 +1,159 @@
+/*
+ * liblookm - one-shot, prefill-time KV-cache compression for multimodal prompts (LOOK-M),
+ * hand-written HIP kernels for gfx950 (MI355X) behind a plain C ABI.
+ *
+ * One call compresses the KV cache of one transformer layer of one prompt.  For every head,
+ * independently (the paper omits head and layer indices, Section 3.1):
+ *   1. accumulated attention scores A_s[j] = sum_i softmax_causal(Q K^T / sqrt(d))[i, j]
+ *      (Section 3.2, Eq. 4; the scale is the one of Eq. 3) - never materialising the L x L matrix;
+ *   2. text-prior selection: text tokens and the last `recent_window` positions are always
+ *      conserved, the rest of the budget goes to the highest-scoring image tokens
+ *      (Section 3.2, Eq. 5-8); equal scores go to the lower position;
+ *   3. every evicted key is matched to its most cosine-similar conserved key
+ *      (Section 3.3, Eq. 9; original keys, ties to the lower position);
+ *   4. evicted K/V rows are merged into their match by the averaged (Eq. 10), pivotal (Eq. 11)
+ *      or weighted (Eq. 12) rule; values reuse the keys' matching and weights;
+ *   5. the conserved, merged rows are written as a compact cache in ascending position order.
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory on the current device; "host" pointers are
+ *     ordinary host memory.  Nothing here takes or returns framework types.
+ *   - Tensors are dense, row-major, innermost stride 1: q, k, v are [H, L, d] (row stride d,
+ *     head stride L*d).  Device tensor pointers must be 16-byte aligned.
+ *   - The library allocates and frees nothing: inputs, outputs and the scratch `workspace` are
+ *     owned by the caller; inputs are never written.  All work is enqueued on `hip_stream`
+ *     (a hipStream_t passed as void*, NULL = the default stream); calls do not synchronise.
+ *   - The return value reports everything the host can check (negative lookm_status); those checks
+ *     run before any kernel is launched and need no GPU.  The one check that needs device data
+ *     (budget smaller than the number of protected positions) is reported through `status_out`.
+ *   - A pointer to an array that is empty for the given sizes (budget 0, or budget = L) may be NULL.
+ *   - Results are deterministic: no floating-point atomics, fixed reduction orders.
+ *   - Supported: dt in {LOOKM_F32, LOOKM_BF16}; d a multiple of 8 with 8 <= d <= 256;
+ *     1 <= L <= LOOKM_MAX_L; H >= 1 with H*L*d below 2^40 elements.
+ */
+#ifndef LOOKM_H
+#define LOOKM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LOOKM_MAX_L 32768
+
+typedef enum {
+    LOOKM_OK = 0,
+    LOOKM_ERR_INVALID_ARG = -1,            /* null pointer, non-positive size, misaligned pointer, bad enum */
+    LOOKM_ERR_UNSUPPORTED = -2,            /* dtype / head_dim / length outside the supported set */
+    LOOKM_ERR_BUDGET_RANGE = -3,           /* budget > L, budget < recent_window, or recent_window > L */
+    LOOKM_ERR_BUDGET_BELOW_PROTECTED = -4, /* budget < |text u recent|: they cannot all be conserved */
+    LOOKM_ERR_WORKSPACE = -5,              /* workspace missing, misaligned or too small */
+    LOOKM_ERR_DEVICE = -6                  /* a HIP runtime call failed */
+} lookm_status;
+
+typedef enum {
+    LOOKM_MERGE_NONE = 0,     /* eviction only: outputs are exact gathers of the conserved rows */
+    LOOKM_MERGE_AVERAGED = 1, /* Eq. 10 */
+    LOOKM_MERGE_PIVOTAL = 2,  /* Eq. 11 */
+    LOOKM_MERGE_WEIGHTED = 3  /* Eq. 12 (taken literally: divisor n+1, weights = matching cosines) */
+} lookm_merge_mode;
+
+typedef enum { LOOKM_F32 = 0, LOOKM_BF16 = 1 } lookm_dtype;
+
+/* Library version string, static storage. */
+const char* lookm_version(void);
+
+/* Human-readable name of a lookm_status value, static storage. */
+const char* lookm_status_string(int status);
+
+/*
+ * Host helper: the number of protected positions |T u R| for a HOST copy of the modality mask
+ * (T = text positions, mask 0; R = the last recent_window positions; Section 3.2).  A caller
+ * sizes `budget` with it: budget = protected + number of image tokens to conserve.
+ * Returns a negative lookm_status on bad arguments.
+ */
+int lookm_protected_count(const uint8_t* mask_host, int L, int recent_window);
+
+/*
+ * Bytes of device scratch that lookm_compress (and each stage call) needs for these sizes;
+ * 0 on invalid sizes.  The workspace must be 256-byte aligned.
+ */
+size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt);
+
+/*
+ * The whole path (Section 3.2 + 3.3) for one layer.
+ *   q, k, v        device, [H, L, d] of dtype dt.
+ *   modality_mask  device, uint8 [L]: 1 = image token (evictable), 0 = text token (always conserved);
+ *                  shared by all heads.  An all-ones mask switches the text prior off.
+ *   budget         B, total rows conserved per head (the paper's S = N + M).  Needs
+ *                  recent_window <= B <= L (else LOOKM_ERR_BUDGET_RANGE) and B >= |T u R|
+ *                  (else *status_out = LOOKM_ERR_BUDGET_BELOW_PROTECTED and outputs are unspecified).
+ *   recent_window  M, the last M positions are always conserved.
+ *   k_out, v_out   device, [H, B, d] of dtype dt; row r of head h is the (merged) row of original
+ *                  position kept_idx[h, r].  fp32 accumulation, one round-to-nearest-even to bf16.
+ *   kept_idx       device, int32 [H, B], strictly ascending original positions.
+ *   scores_out     device, float [H, L], the raw A_s of Eq. 4 (no text prior added), or NULL.
+ *   status_out     device, int32 [1]: LOOKM_OK or LOOKM_ERR_BUDGET_BELOW_PROTECTED. Must not be NULL.
+ *   workspace      device scratch of at least lookm_workspace_bytes(H, L, d, budget, dt) bytes.
+ */
+int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                   int H, int L, int d, lookm_dtype dt,
+                   int budget, int recent_window, lookm_merge_mode merge_mode,
+                   void* k_out, void* v_out, int32_t* kept_idx,
+                   float* scores_out, int32_t* status_out,
+                   void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- the stages of the path, callable one by one (same conventions) ------------------------------ */
+
+/*
+ * Eq. 4: scores_out[h, j] = sum over rows i >= j of exp(q_i.k_j/sqrt(d) - lse_i), where lse_i is the
+ * log-sum-exp of row i over columns <= i.  Two flash-style passes over Q K^T (row log-sum-exp, then
+ * column sums); bf16 inputs with d = 128 run on the matrix cores with fp32 accumulation.
+ *   scores_out  device, float [H, L].
+ */
+int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt,
+                 float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Eq. 5-8: per head, conserve every text position, the last recent_window positions, and the
+ * budget - |T u R| image positions outside the window with the highest score (ties -> lower position).
+ * The text prior of Eq. 5 is realised as a ranking class (text above any image token), not as a
+ * floating-point addition.
+ *   scores       device, float [H, L] (any finite values; compared as IEEE floats).
+ *   kept_idx     device, int32 [H, budget] ascending.   evicted_idx  device, int32 [H, L - budget] ascending.
+ *   status_out   device, int32 [1], as in lookm_compress.
+ */
+int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L,
+                 int budget, int recent_window,
+                 int32_t* kept_idx, int32_t* evicted_idx, int32_t* status_out, void* hip_stream);
+
+/*
+ * Eq. 9: for every evicted position e of head h, the slot r in [0, budget) of the conserved key with
+ * the highest cosine similarity to key e (original keys; ties -> lower slot, i.e. lower position;
+ * a zero-norm key has cosine 0 with everything), and that cosine.
+ *   kept_idx, evicted_idx  device, as produced by lookm_select (in-range, ascending).
+ *   assign  device, int32 [H, L - budget].   sim  device, float [H, L - budget].
+ */
+int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted_idx,
+                  int H, int L, int d, lookm_dtype dt, int budget,
+                  int32_t* assign, float* sim,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Eq. 10-12 + compaction: x_out[h, r] = merge of row kept_idx[h, r] of x with the rows
+ * {evicted_idx[h, e] : assign[h, e] = r}, taken in ascending position, for x in {k, v}.
+ *   assign  device, int32 [H, L - budget], values in [0, budget).   sim  device, float [H, L - budget]
+ *   (read only by LOOKM_MERGE_WEIGHTED).
+ */
+int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int32_t* evicted_idx,
+                const int32_t* assign, const float* sim,
+                int H, int L, int d, lookm_dtype dt, int budget, lookm_merge_mode merge_mode,
+                void* k_out, void* v_out,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LOOKM_H */

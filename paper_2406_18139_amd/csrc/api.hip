@@ -1,0 +1,199 @@
+// C ABI of liblookm: argument validation (host-only, before any launch), workspace carving and the
+// launch sequence of the compression path.  See include/lookm.h for the contract.
+#include "common.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t lse, scores, evicted, assign, sim, rnorm, offsets, members, total;
+};
+
+Layout make_layout(int H, int L, int budget)
+{
+    const size_t HL = (size_t)H * L, HE = (size_t)H * (size_t)(L - budget);
+    Layout w;
+    size_t o = 0;
+    w.lse = o;     o += align_up(HL * sizeof(float));
+    w.scores = o;  o += align_up(HL * sizeof(float));
+    w.evicted = o; o += align_up(HE * sizeof(int32_t));
+    w.assign = o;  o += align_up(HE * sizeof(int32_t));
+    w.sim = o;     o += align_up(HE * sizeof(float));
+    w.rnorm = o;   o += align_up(HL * sizeof(float));
+    w.offsets = o; o += align_up((size_t)H * (budget + 1) * sizeof(int32_t));
+    w.members = o; o += align_up(HE * sizeof(int32_t));
+    w.total = o;
+    return w;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_shape(int H, int L, int d, int dt)
+{
+    if (H <= 0 || L <= 0 || d <= 0) return LOOKM_ERR_INVALID_ARG;
+    if (dt != LOOKM_F32 && dt != LOOKM_BF16) return LOOKM_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 256 || L > LOOKM_MAX_L) return LOOKM_ERR_UNSUPPORTED;
+    if ((double)H * (double)L * (double)d >= 1099511627776.0) return LOOKM_ERR_UNSUPPORTED;
+    return LOOKM_OK;
+}
+
+int check_budget(int L, int budget, int M)
+{
+    if (M < 0 || budget < 0) return LOOKM_ERR_INVALID_ARG;
+    if (M > L || budget > L || budget < M) return LOOKM_ERR_BUDGET_RANGE;
+    return LOOKM_OK;
+}
+
+int check_workspace(const void* ws, size_t bytes, int H, int L, int budget)
+{
+    if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return LOOKM_ERR_WORKSPACE;
+    if (bytes < make_layout(H, L, budget).total) return LOOKM_ERR_WORKSPACE;
+    return LOOKM_OK;
+}
+
+template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
+
+}  // namespace
+
+extern "C" {
+
+const char* lookm_version(void) { return "lookm 0.1 (gfx950)"; }
+
+const char* lookm_status_string(int status)
+{
+    switch (status) {
+        case LOOKM_OK: return "ok";
+        case LOOKM_ERR_INVALID_ARG: return "invalid argument";
+        case LOOKM_ERR_UNSUPPORTED: return "unsupported dtype, head_dim or length";
+        case LOOKM_ERR_BUDGET_RANGE: return "budget or recent_window out of range";
+        case LOOKM_ERR_BUDGET_BELOW_PROTECTED: return "budget smaller than text plus recent window";
+        case LOOKM_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LOOKM_ERR_DEVICE: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int lookm_protected_count(const uint8_t* mask_host, int L, int recent_window)
+{
+    if (mask_host == nullptr || L <= 0 || recent_window < 0) return LOOKM_ERR_INVALID_ARG;
+    if (recent_window > L) return LOOKM_ERR_BUDGET_RANGE;
+    int n = 0;
+    for (int j = 0; j < L; ++j) n += (mask_host[j] == 0 || j >= L - recent_window) ? 1 : 0;
+    return n;
+}
+
+size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
+{
+    if (check_shape(H, L, d, (int)dt) != LOOKM_OK || budget < 0 || budget > L) return 0;
+    return make_layout(H, L, budget).total;
+}
+
+int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !k || !scores_out) return LOOKM_ERR_INVALID_ARG;
+    int rc = check_shape(H, L, d, (int)dt);
+    if (rc != LOOKM_OK) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(scores_out)) return LOOKM_ERR_INVALID_ARG;
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+        workspace_bytes < align_up((size_t)H * L * sizeof(float)))
+        return LOOKM_ERR_WORKSPACE;
+    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, 0), scores_out, (hipStream_t)hip_stream);
+}
+
+int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L, int budget, int recent_window,
+                 int32_t* kept_idx, int32_t* evicted_idx, int32_t* status_out, void* hip_stream)
+{
+    if (!scores || !modality_mask || !status_out) return LOOKM_ERR_INVALID_ARG;
+    if (H <= 0 || L <= 0) return LOOKM_ERR_INVALID_ARG;
+    if (L > LOOKM_MAX_L) return LOOKM_ERR_UNSUPPORTED;
+    int rc = check_budget(L, budget, recent_window);
+    if (rc != LOOKM_OK) return rc;
+    // an empty list (budget 0, or budget L) may be passed as NULL
+    if ((budget > 0 && !kept_idx) || (budget < L && !evicted_idx)) return LOOKM_ERR_INVALID_ARG;
+    return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted_idx,
+                                     status_out, (hipStream_t)hip_stream);
+}
+
+int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted_idx, int H, int L, int d,
+                  lookm_dtype dt, int budget, int32_t* assign, float* sim, void* workspace, size_t workspace_bytes,
+                  void* hip_stream)
+{
+    if (!k || !kept_idx) return LOOKM_ERR_INVALID_ARG;
+    int rc = check_shape(H, L, d, (int)dt);
+    if (rc != LOOKM_OK) return rc;
+    if (budget < 1 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
+    if (budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;   // empty lists may be NULL
+    if (!aligned16(k)) return LOOKM_ERR_INVALID_ARG;
+    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    if (rc != LOOKM_OK) return rc;
+    const Layout w = make_layout(H, L, budget);
+    return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
+                                      assign, sim, (hipStream_t)hip_stream);
+}
+
+int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int32_t* evicted_idx,
+                const int32_t* assign, const float* sim, int H, int L, int d, lookm_dtype dt, int budget,
+                lookm_merge_mode merge_mode, void* k_out, void* v_out, void* workspace, size_t workspace_bytes,
+                void* hip_stream)
+{
+    if (!k || !v) return LOOKM_ERR_INVALID_ARG;
+    if (budget > 0 && (!kept_idx || !k_out || !v_out)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
+    if ((int)merge_mode < LOOKM_MERGE_NONE || (int)merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
+    int rc = check_shape(H, L, d, (int)dt);
+    if (rc != LOOKM_OK) return rc;
+    if (budget < 0 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
+    if (merge_mode != LOOKM_MERGE_NONE && budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;
+    if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return LOOKM_ERR_INVALID_ARG;
+    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    if (rc != LOOKM_OK) return rc;
+    const Layout w = make_layout(H, L, budget);
+    return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
+                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.members), k_out, v_out,
+                                    (hipStream_t)hip_stream);
+}
+
+int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L, int d,
+                   lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode, void* k_out,
+                   void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !k || !v || !modality_mask || !status_out) return LOOKM_ERR_INVALID_ARG;
+    if (budget > 0 && (!k_out || !v_out || !kept_idx)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
+    if ((int)merge_mode < LOOKM_MERGE_NONE || (int)merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
+    int rc = check_shape(H, L, d, (int)dt);
+    if (rc != LOOKM_OK) return rc;
+    rc = check_budget(L, budget, recent_window);
+    if (rc != LOOKM_OK) return rc;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
+        (scores_out && !aligned16(scores_out)))
+        return LOOKM_ERR_INVALID_ARG;
+    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    if (rc != LOOKM_OK) return rc;
+
+    const Layout w = make_layout(H, L, budget);
+    hipStream_t st = (hipStream_t)hip_stream;
+    float* scores = scores_out ? scores_out : at<float>(workspace, w.scores);
+    int32_t* evicted = at<int32_t>(workspace, w.evicted);
+    int32_t* assign = at<int32_t>(workspace, w.assign);
+    float* sim = at<float>(workspace, w.sim);
+
+    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores, st);
+    if (rc != LOOKM_OK) return rc;
+    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
+    if (rc != LOOKM_OK) return rc;
+    if (merge_mode != LOOKM_MERGE_NONE && budget < L) {
+        if (budget == 0) return LOOKM_OK;   // nothing conserved: nothing to merge into
+        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
+                                        assign, sim, st);
+        if (rc != LOOKM_OK) return rc;
+    }
+    return lookm_host::launch_merge(k, v, kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)merge_mode,
+                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.members), k_out, v_out,
+                                    st);
+}
+
+}  // extern "C"

@@ -1,0 +1,236 @@
+"""ctypes binding of liblookm.so: argument marshalling only.
+
+Every function has the name and the semantics of the C entry point it forwards to (see
+include/lookm.h).  PyTorch is used for device memory and for the current HIP stream; all of the
+method's arithmetic runs in the library's kernels.  There is no CPU fallback: a missing library
+or a non-GPU tensor raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from pathlib import Path
+from typing import Optional
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "liblookm.so"
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_UNSUPPORTED = -2
+ERR_BUDGET_RANGE = -3
+ERR_BUDGET_BELOW_PROTECTED = -4
+ERR_WORKSPACE = -5
+ERR_DEVICE = -6
+
+MERGE_MODES = {"none": 0, "averaged": 1, "pivotal": 2, "weighted": 3}
+F32, BF16 = 0, 1
+
+EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
+           "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge"]
+
+
+class LookmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} ({code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads liblookm.so (built by ``python -m paper_2406_18139_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2406_18139_amd.build`")
+        L = ctypes.CDLL(str(LIB_PATH))
+        vp, I, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.lookm_version.restype = ctypes.c_char_p
+        L.lookm_version.argtypes = []
+        L.lookm_status_string.restype = ctypes.c_char_p
+        L.lookm_status_string.argtypes = [I]
+        L.lookm_protected_count.restype = I
+        L.lookm_protected_count.argtypes = [vp, I, I]
+        L.lookm_workspace_bytes.restype = sz
+        L.lookm_workspace_bytes.argtypes = [I, I, I, I, I]
+        L.lookm_compress.restype = I
+        L.lookm_compress.argtypes = [vp, vp, vp, vp, I, I, I, I, I, I, I, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lookm_scores.restype = I
+        L.lookm_scores.argtypes = [vp, vp, I, I, I, I, vp, vp, sz, vp]
+        L.lookm_select.restype = I
+        L.lookm_select.argtypes = [vp, vp, I, I, I, I, vp, vp, vp, vp]
+        L.lookm_nearest.restype = I
+        L.lookm_nearest.argtypes = [vp, vp, vp, I, I, I, I, I, vp, vp, vp, sz, vp]
+        L.lookm_merge.restype = I
+        L.lookm_merge.argtypes = [vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, vp, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().lookm_version().decode()
+
+
+def status_string(code: int) -> str:
+    return lib().lookm_status_string(int(code)).decode()
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU (no CPU path exists)")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _mode(m) -> int:
+    return MERGE_MODES[m] if isinstance(m, str) else int(m)
+
+
+def protected_count(mask_host, recent_window: int) -> int:
+    """lookm_protected_count on a host mask (torch CPU tensor / numpy array / bytes-like of uint8)."""
+    m = torch.as_tensor(mask_host, dtype=torch.uint8).contiguous().cpu()
+    rc = lib().lookm_protected_count(m.data_ptr(), m.numel(), int(recent_window))
+    if rc < 0:
+        raise LookmError(rc, "lookm_protected_count")
+    return rc
+
+
+def workspace_bytes(H: int, L: int, d: int, budget: int, dt: int) -> int:
+    return int(lib().lookm_workspace_bytes(H, L, d, budget, dt))
+
+
+def alloc_workspace(H: int, L: int, d: int, budget: int, dt: int, device) -> torch.Tensor:
+    n = workspace_bytes(H, L, d, budget, dt)
+    if n == 0:
+        raise LookmError(ERR_INVALID_ARG, "lookm_workspace_bytes")
+    return torch.empty(n + 256, dtype=torch.uint8, device=device)
+
+
+def _ws_ptr(ws: torch.Tensor):
+    p = ws.data_ptr()
+    a = (p + 255) // 256 * 256
+    return a, ws.numel() - (a - p)
+
+
+@dataclass
+class Compressed:
+    k_out: torch.Tensor       # [H, B, d]
+    v_out: torch.Tensor       # [H, B, d]
+    kept_idx: torch.Tensor    # [H, B] int32
+    scores: Optional[torch.Tensor]   # [H, L] float32 or None
+    status: torch.Tensor      # [1] int32 (device)
+
+
+def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode,
+                   want_scores: bool = False, out: Optional[Compressed] = None,
+                   workspace: Optional[torch.Tensor] = None, check: bool = True) -> Compressed:
+    """One layer's compression.  q, k, v: GPU tensors [H, L, d]; modality_mask: GPU uint8 [L].
+    ``check=True`` synchronises to read the device status word and raises on failure."""
+    H, L, d = q.shape
+    dt = _dt(q)
+    B = int(budget)
+    dev = q.device
+    if out is None:
+        nb = max(B, 0)
+        out = Compressed(torch.empty((H, nb, d), dtype=q.dtype, device=dev),
+                         torch.empty((H, nb, d), dtype=q.dtype, device=dev),
+                         torch.empty((H, nb), dtype=torch.int32, device=dev),
+                         torch.empty((H, L), dtype=torch.float32, device=dev) if want_scores else None,
+                         torch.zeros(1, dtype=torch.int32, device=dev))
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, min(max(B, 0), L), dt, dev)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_compress(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
+                              H, L, d, dt, B, int(recent_window), _mode(merge_mode),
+                              _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"), _dev(out.kept_idx, "kept_idx"),
+                              _dev(out.scores, "scores") if out.scores is not None else None,
+                              _dev(out.status, "status"), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_compress")
+    if check:
+        st = int(out.status.item())
+        if st != OK:
+            raise LookmError(st, "lookm_compress (device)")
+    return out
+
+
+def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    H, L, d = q.shape
+    dt = _dt(q)
+    scores = torch.empty((H, L), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, 0, dt, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_scores(_dev(q, "q"), _dev(k, "k"), H, L, d, dt, scores.data_ptr(), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_scores")
+    return scores
+
+
+def lookm_select(scores, modality_mask, budget: int, recent_window: int, check: bool = True):
+    H, L = scores.shape
+    B = int(budget)
+    dev = scores.device
+    kept = torch.empty((H, max(B, 0)), dtype=torch.int32, device=dev)
+    evicted = torch.empty((H, max(L - B, 0)), dtype=torch.int32, device=dev)
+    status = torch.zeros(1, dtype=torch.int32, device=dev)
+    rc = lib().lookm_select(_dev(scores, "scores"), _dev(modality_mask, "modality_mask"), H, L, B,
+                            int(recent_window), kept.data_ptr(), evicted.data_ptr(), status.data_ptr(), _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_select")
+    if check:
+        st = int(status.item())
+        if st != OK:
+            raise LookmError(st, "lookm_select (device)")
+    return kept, evicted
+
+
+def lookm_nearest(k, kept_idx, evicted_idx, workspace: Optional[torch.Tensor] = None):
+    H, L, d = k.shape
+    B = kept_idx.shape[1]
+    dt = _dt(k)
+    Le = L - B
+    assign = torch.empty((H, Le), dtype=torch.int32, device=k.device)
+    sim = torch.empty((H, Le), dtype=torch.float32, device=k.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, B, dt, k.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_nearest(_dev(k, "k"), _dev(kept_idx, "kept_idx"), _dev(evicted_idx, "evicted_idx"), H, L, d, dt,
+                             B, assign.data_ptr(), sim.data_ptr(), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_nearest")
+    return assign, sim
+
+
+def lookm_merge(k, v, kept_idx, evicted_idx, assign, sim, merge_mode, workspace: Optional[torch.Tensor] = None):
+    H, L, d = k.shape
+    B = kept_idx.shape[1]
+    dt = _dt(k)
+    k_out = torch.empty((H, B, d), dtype=k.dtype, device=k.device)
+    v_out = torch.empty((H, B, d), dtype=k.dtype, device=k.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, B, dt, k.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_merge(_dev(k, "k"), _dev(v, "v"), _dev(kept_idx, "kept_idx"), _dev(evicted_idx, "evicted_idx"),
+                           _dev(assign, "assign"), _dev(sim, "sim"), H, L, d, dt, B, _mode(merge_mode),
+                           k_out.data_ptr(), v_out.data_ptr(), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_merge")
+    return k_out, v_out

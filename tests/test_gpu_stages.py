@@ -1,0 +1,203 @@
+"""GPU parity, stage by stage, through the C ABI: each kernel against the oracle function for the
+same step, on sizes that span several tiles and a ragged tail, plus the degenerate cases."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2406_18139_amd import lookm
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def rand_qk(H, L, d, dtype, seed, scale=1.0):
+    g = torch.Generator().manual_seed(seed)
+    q = (torch.randn(H, L, d, generator=g) * scale).to(dtype)
+    k = (torch.randn(H, L, d, generator=g) * scale).to(dtype)
+    return q, k
+
+
+@pytest.mark.parametrize("H,L,d,dtype", [
+    (3, 700, 128, torch.bfloat16),      # matrix-core path: 3 strips of 256, ragged tail
+    (2, 256, 128, torch.bfloat16),      # exactly one strip
+    (1, 1, 128, torch.bfloat16),        # single token
+    (2, 65, 128, torch.bfloat16),
+    (2, 333, 64, torch.bfloat16),       # portable path, bf16
+    (2, 256, 64, torch.float32),        # the tiny configuration's shape
+    (1, 130, 8, torch.float32),
+    (1, 97, 256, torch.float32),
+])
+def test_scores_match_oracle(H, L, d, dtype):
+    q, k = rand_qk(H, L, d, dtype, seed=L * 7 + d)
+    s = lookm.lookm_scores(q.cuda(), k.cuda()).cpu().numpy().astype(np.float64)
+    ref = oracle.scores(q, k)
+    rel = np.abs(s - ref) / ref
+    print(f"scores H={H} L={L} d={d} {dtype}: max rel err {rel.max():.3e}")
+    assert rel.max() < 2e-5        # far inside the 1e-3 bar
+    np.testing.assert_allclose(s.sum(1), L, rtol=1e-5)
+
+
+def test_scores_large_logits_and_determinism():
+    q, k = rand_qk(2, 600, 128, torch.bfloat16, seed=5, scale=4.0)   # logits up to ~ +-60
+    a = lookm.lookm_scores(q.cuda(), k.cuda())
+    b = lookm.lookm_scores(q.cuda(), k.cuda())
+    assert torch.equal(a, b)
+    ref = oracle.scores(q, k)
+    s = a.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(s))
+    big = ref > 1e-6
+    assert (np.abs(s - ref)[big] / ref[big]).max() < 1e-4
+    np.testing.assert_allclose(s.sum(1), 600, rtol=1e-5)
+
+
+def test_scores_zero_queries_closed_form():
+    L = 1000
+    q = torch.zeros(1, L, 128, dtype=torch.bfloat16)
+    k = torch.randn(1, L, 128, generator=torch.Generator().manual_seed(1)).to(torch.bfloat16)
+    s = lookm.lookm_scores(q.cuda(), k.cuda()).cpu().numpy()[0].astype(np.float64)
+    inv = 1.0 / np.arange(1, L + 1)
+    np.testing.assert_allclose(s, np.cumsum(inv[::-1])[::-1], rtol=2e-6)
+
+
+def select_case(scores, mask, B, M):
+    sg = torch.from_numpy(np.asarray(scores, np.float32)).cuda()
+    mg = torch.from_numpy(np.asarray(mask, np.uint8)).cuda()
+    kept, ev = lookm.lookm_select(sg, mg, B, M)
+    return kept.cpu().numpy(), ev.cpu().numpy()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_select_matches_oracle_with_ties(seed):
+    rng = np.random.default_rng(seed)
+    H = 3
+    L = int(rng.integers(1, 5000))
+    M = int(rng.integers(0, min(L, 70) + 1))
+    mask = (rng.random(L) < 0.8).astype(np.uint8)
+    coarse = seed % 2 == 0
+    scores = (rng.integers(1, 40, (H, L)) / 8.0 if coarse else rng.random((H, L)) + 1e-3).astype(np.float32)
+    P = oracle.protected_count(mask, M)
+    for B in sorted({P, min(L, P + 1), (P + L) // 2, max(P, L - 1), L}):
+        kept, ev = select_case(scores, mask, B, M)
+        for h in range(H):
+            rk, re_ = oracle.select(scores[h].astype(np.float64), mask, B, M)
+            assert kept[h].tolist() == rk.tolist(), (L, M, B, h)
+            assert ev[h].tolist() == re_.tolist(), (L, M, B, h)
+
+
+def test_select_degenerate_cases():
+    L = 300
+    scores = np.random.default_rng(0).random((2, L)).astype(np.float32)
+    ones = np.ones(L, np.uint8)
+    kept, ev = select_case(scores, ones, 0, 0)                      # nothing conserved
+    assert kept.shape == (2, 0) and ev[0].tolist() == list(range(L))
+    kept, ev = select_case(scores, ones, L, L)                      # the window is the whole prompt
+    assert kept[1].tolist() == list(range(L)) and ev.shape == (2, 0)
+    kept, _ = select_case(scores, np.zeros(L, np.uint8), L, 0)      # all text
+    assert kept[0].tolist() == list(range(L))
+    kept, _ = select_case(scores, ones, 40, 0)                      # text prior off: plain top-B
+    for h in range(2):
+        assert kept[h].tolist() == np.sort(np.argsort(-scores[h], kind="stable")[:40]).tolist()
+    neg = -scores                                                   # negative and zero scores order correctly
+    neg[:, 5] = 0.0
+    neg[:, 6] = -0.0
+    kept, _ = select_case(neg, ones, 3, 0)
+    for h in range(2):
+        assert kept[h].tolist() == oracle.select(neg[h].astype(np.float64), ones, 3, 0)[0].tolist()
+
+
+def test_select_reports_budget_below_protected():
+    L = 64
+    mask = np.zeros(L, np.uint8)
+    mask[10:50] = 1
+    sg = torch.rand(2, L, device="cuda")
+    with pytest.raises(lookm.LookmError) as e:
+        lookm.lookm_select(sg, torch.from_numpy(mask).cuda(), 20, 4)   # 24 text + 4 recent (text) -> 24 > 20
+    assert e.value.code == lookm.ERR_BUDGET_BELOW_PROTECTED
+
+
+def split(L, B, seed):
+    rng = np.random.default_rng(seed)
+    kept = np.sort(rng.choice(L, B, replace=False)).astype(np.int32)
+    return kept, np.setdiff1d(np.arange(L, dtype=np.int32), kept)
+
+
+@pytest.mark.parametrize("H,L,B,d,dtype", [
+    (2, 900, 200, 128, torch.bfloat16),    # matrix-core path: ragged conserved and evicted tiles
+    (2, 600, 64, 128, torch.bfloat16),
+    (1, 300, 1, 128, torch.bfloat16),      # one conserved key
+    (1, 300, 299, 128, torch.bfloat16),    # one evicted key
+    (2, 500, 130, 64, torch.bfloat16),     # portable path
+    (2, 256, 154, 64, torch.float32),
+    (1, 100, 30, 8, torch.float32),
+])
+def test_nearest_matches_oracle(H, L, B, d, dtype):
+    g = torch.Generator().manual_seed(L + B)
+    cent = torch.randn(H, 16, d, generator=g)
+    k = (cent[:, torch.randint(0, 16, (L,), generator=g)] + 0.3 * torch.randn(H, L, d, generator=g)).to(dtype)
+    kept = np.stack([split(L, B, 10 + h)[0] for h in range(H)])
+    ev = np.stack([split(L, B, 10 + h)[1] for h in range(H)])
+    a, s = lookm.lookm_nearest(k.cuda(), torch.from_numpy(kept).cuda(), torch.from_numpy(ev).cuda())
+    a, s = a.cpu().numpy(), s.cpu().numpy()
+    kf = k.float().numpy()
+    ties = sum(parity.check_nearest(kf[h], kept[h], ev[h], a[h], s[h]) for h in range(H))
+    print(f"nearest H={H} L={L} B={B} d={d}: {ties} tie-band rows")
+    assert ties <= 2
+
+
+def test_nearest_exact_ties_and_zero_keys():
+    L, d = 200, 128
+    g = torch.Generator().manual_seed(3)
+    k = torch.randn(1, L, d, generator=g).to(torch.bfloat16)
+    kept, ev = split(L, 50, 4)
+    k[0, kept[7]] = k[0, kept[3]]                   # duplicate conserved keys: lower slot must win
+    k[0, kept[30]] = k[0, kept[3]] * 2
+    k[0, ev[5]] = k[0, kept[3]] * 0.5
+    k[0, ev[9]] = 0                                 # zero evicted key: cosine 0 with everything -> slot 0
+    k[0, kept[0]] = 0                               # zero conserved key
+    a, s = lookm.lookm_nearest(k.cuda(), torch.from_numpy(kept)[None].cuda(), torch.from_numpy(ev)[None].cuda())
+    a, s = a.cpu().numpy()[0], s.cpu().numpy()[0]
+    ra, rs = oracle.nearest(k[0], kept, ev)
+    assert a[5] == 3 and ra[5] == 3 and abs(s[5] - 1.0) < 1e-6
+    assert a[9] == 0 and ra[9] == 0 and s[9] == 0.0
+    assert (a == ra).mean() > 0.97
+
+
+@pytest.mark.parametrize("mode", ["averaged", "pivotal", "weighted", "none"])
+@pytest.mark.parametrize("H,L,B,d,dtype", [
+    (2, 700, 150, 128, torch.bfloat16),
+    (2, 256, 154, 64, torch.float32),
+    (1, 120, 40, 8, torch.float32),
+    (1, 300, 77, 256, torch.bfloat16),
+])
+def test_merge_matches_oracle(mode, H, L, B, d, dtype):
+    g = torch.Generator().manual_seed(L * 3 + B)
+    k = torch.randn(H, L, d, generator=g).to(dtype)
+    v = (torch.randn(H, L, d, generator=g) * 2).to(dtype)
+    rng = np.random.default_rng(B)
+    kept = np.stack([split(L, B, 20 + h)[0] for h in range(H)])
+    ev = np.stack([split(L, B, 20 + h)[1] for h in range(H)])
+    # skewed assignment: a few slots collect many members, many collect none
+    assign = np.minimum((rng.random((H, L - B)) ** 3 * B).astype(np.int32), B - 1)
+    sim = rng.uniform(0.1, 1.0, (H, L - B)).astype(np.float32)
+    ko, vo = lookm.lookm_merge(k.cuda(), v.cuda(), torch.from_numpy(kept).cuda(), torch.from_numpy(ev).cuda(),
+                               torch.from_numpy(assign).cuda(), torch.from_numpy(sim).cuda(), mode)
+    ko, vo = ko.float().cpu().numpy(), vo.float().cpu().numpy()
+    for h in range(H):
+        parity.check_merge(k[h].float().numpy(), kept[h], ev[h], assign[h], sim[h], mode, ko[h], dtype)
+        parity.check_merge(v[h].float().numpy(), kept[h], ev[h], assign[h], sim[h], mode, vo[h], dtype)
+
+
+def test_merge_everything_into_one_slot():
+    # the worst skew: all evicted rows matched to one conserved row
+    H, L, B, d = 1, 2000, 10, 128
+    g = torch.Generator().manual_seed(9)
+    k = torch.randn(H, L, d, generator=g).to(torch.bfloat16)
+    kept, ev = split(L, B, 1)
+    assign = np.full((1, L - B), 4, np.int32)
+    sim = np.full((1, L - B), 0.5, np.float32)
+    ko, vo = lookm.lookm_merge(k.cuda(), k.cuda(), torch.from_numpy(kept)[None].cuda(), torch.from_numpy(ev)[None].cuda(),
+                               torch.from_numpy(assign).cuda(), torch.from_numpy(sim).cuda(), "averaged")
+    parity.check_merge(k[0].float().numpy(), kept, ev, assign[0], sim[0], "averaged", ko[0].float().cpu().numpy(),
+                       torch.bfloat16)
+    assert torch.equal(ko, vo)
