@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the LOOK-M prefill-time KV-cache compression path on one MI355X.
+
+A "step" is one lookm_compress call: every kernel of the path (two score passes, selection, key
+norms, cosine matching, similarity sets, merge + compaction) over all heads of one layer of the
+headline workload (20 images x 576 tokens interleaved with 21 text spans, L = 12 644, 32 heads,
+head_dim 128, bf16, budget = text + recent + 10 % of the evictable image tokens, pivotal merging).
+Inputs are seeded synthetic tensors, resident in HBM before the timed region.
+
+Prints ONE JSON line: throughput (prompt KV tokens compressed per second per layer), the roofline of
+the dominant kernel (measured live with HIP events on the launch stream), per-kernel figures, and the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+from paper_2406_18139_amd import lookm
+from paper_2406_18139_amd import workloads as W
+
+PEAK_MFMA_BF16 = 2.5e15   # dense bf16 MFMA, FLOP/s
+PEAK_HBM = 8.0e12         # B/s
+
+
+def algorithmic_work(w: W.Workload) -> dict:
+    """Work the method needs per launch of each kernel (all heads of one layer); nothing a particular
+    tiling adds (masked halves of diagonal tiles, padding, re-reads) is counted."""
+    H, L, d, B = w.H, w.L, w.d, w.budget()
+    Le = L - B
+    e = 2 if w.dtype == "bf16" else 4
+    pairs = L * (L + 1) // 2
+    return {
+        "score_lse": ("mfma", 2.0 * d * pairs * H),
+        "score_colsum": ("mfma", 2.0 * d * pairs * H),
+        "select": ("hbm", H * (4.0 * L + 4.0 * B + 4.0 * Le) + L),
+        "rnorm": ("hbm", H * (L * d * e + 4.0 * L)),
+        "nearest": ("mfma", 2.0 * d * Le * B * H),
+        "bucket": ("hbm", H * (4.0 * Le + 4.0 * (B + 1) + 4.0 * Le)),
+        "merge": ("hbm", H * (2.0 * L * d * e + 2.0 * B * d * e + 4.0 * B + 12.0 * Le + 4.0 * (B + 1))),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", default="long", choices=["long", "long_total", "llava7b"])
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+              "(the path shards over heads / layers / prompts with no exchange; see DESIGN.md).", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the compression path has no CPU fallback.", file=sys.stderr)
+        return 2
+
+    w = {"long": W.LONG, "long_total": W.LONG_TOTAL, "llava7b": W.LLAVA7B}[args.workload]
+    mode = w.modes[0]
+    B, M = w.budget(), w.M
+    q, k, v, mask = W.generate(w)
+    dev = torch.device("cuda:0")
+    qg, kg, vg, mg = (t.to(dev) for t in (q, k, v, mask))
+    out = lookm.alloc_outputs(w.H, w.L, w.d, B, qg.dtype, dev)
+    ws = lookm.alloc_workspace(w.H, w.L, w.d, B, lookm.BF16 if w.dtype == "bf16" else lookm.F32, dev)
+
+    def step():
+        lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    status = int(out.status.item())
+    if status != 0:
+        print(f"bench.py: device status {status}", file=sys.stderr)
+        return 1
+
+    # per-kernel durations: HIP events recorded by the library on the launch stream, same inputs
+    kms = lookm.lookm_compress_profile(qg, kg, vg, mg, B, M, mode, max(args.steps, 1), out, ws)
+    work = algorithmic_work(w)
+    kernels = {}
+    for name, ms in kms.items():
+        bound, amount = work[name]
+        peak = PEAK_MFMA_BF16 if bound == "mfma" else PEAK_HBM
+        ach = amount / (ms * 1e-3) if ms > 0 else 0.0
+        kernels[name] = {"ms": round(ms, 5), "bound": bound,
+                         "achieved": round(ach / (1e12 if bound == "mfma" else 1e9), 3),
+                         "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": round(ach / peak, 4)}
+    dominant = max(kms, key=kms.get)
+    dbound, damount = work[dominant]
+    dpeak = PEAK_MFMA_BF16 if dbound == "mfma" else PEAK_HBM
+    dach = damount / (kms[dominant] * 1e-3)
+    roofline = {"kernel": dominant, "bound": dbound,
+                "achieved": round(dach / (1e12 if dbound == "mfma" else 1e9), 3),
+                "peak": dpeak / (1e12 if dbound == "mfma" else 1e9),
+                "unit": "TFLOP/s" if dbound == "mfma" else "GB/s",
+                "frac": round(dach / dpeak, 4), "traffic": None}
+    score_ms = kms["score_lse"] + kms["score_colsum"]
+    smc_ms = kms["select"] + kms["bucket"] + kms["merge"]
+    smc_bytes = work["select"][1] + work["bucket"][1] + work["merge"][1]
+    groups = {
+        "score_passes": {"ms": round(score_ms, 4), "frac_mfma_peak": round(
+            (work["score_lse"][1] + work["score_colsum"][1]) / (score_ms * 1e-3) / PEAK_MFMA_BF16, 4)},
+        "select_bucket_merge": {"ms": round(smc_ms, 4), "GB/s": round(smc_bytes / (smc_ms * 1e-3) / 1e9, 1),
+                                "frac_hbm_peak": round(smc_bytes / (smc_ms * 1e-3) / PEAK_HBM, 4)},
+    }
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.num_threads()
+        n_heads = max(1, min(w.H, threads))
+        t1 = time.perf_counter()
+        oracle.compress(q[:n_heads], k[:n_heads], v[:n_heads], mask.numpy(), B, M, mode)
+        sec = time.perf_counter() - t1
+        layer_sec = sec * w.H / n_heads
+        cpu_baseline = {"value": round(w.L / layer_sec, 3), "unit": "tokens/s/layer", "cores": min(threads, n_heads),
+                        "kind": "oracle", "seconds": round(sec, 2),
+                        "sample": f"heads 0..{n_heads - 1} of {w.H} of the same layer (one head per thread), "
+                                  f"scaled by {w.H}/{n_heads} to the whole layer"}
+
+    line = {
+        "metric": "prompt KV tokens compressed/sec per layer (12K ctx)",
+        "value": round(w.L / (ms_per_step * 1e-3), 1),
+        "unit": "tokens/s/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.H} heads x d{w.d} {w.dtype}, {w.n_img} images x {w.img_tokens} tokens + "
+                               f"{len(w.spans)} text spans, L={w.L}, budget B={B} (k_img={w.k_img()}), "
+                               f"recent_window={M}, merge={mode}",
+                   "H": w.H, "L": w.L, "d": w.d, "budget": B, "recent_window": M, "merge_mode": mode},
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "kernels": kernels,
+        "groups": groups,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -153,6 +153,29 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
                 void* k_out, void* v_out,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- measurement aid ------------------------------------------------------------------------------- */
+
+/* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;
+ * Section 3.3: key norms, matching, similarity sets, merge + compaction). */
+enum {
+    LOOKM_K_SCORE_LSE = 0, LOOKM_K_SCORE_COLSUM = 1, LOOKM_K_SELECT = 2, LOOKM_K_RNORM = 3,
+    LOOKM_K_NEAREST = 4, LOOKM_K_BUCKET = 5, LOOKM_K_MERGE = 6, LOOKM_N_KERNELS = 7
+};
+
+/*
+ * lookm_compress, run `reps` times with a HIP event recorded on `hip_stream` after every kernel.
+ * Unlike every other call it SYNCHRONISES the stream (once per repetition) and creates / destroys
+ * HIP events.  kernel_ms_host: host, float [LOOKM_N_KERNELS], average milliseconds per kernel
+ * (0 for a kernel the given sizes skip).  All other arguments and results as for lookm_compress.
+ */
+int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                           int H, int L, int d, lookm_dtype dt,
+                           int budget, int recent_window, lookm_merge_mode merge_mode,
+                           void* k_out, void* v_out, int32_t* kept_idx,
+                           float* scores_out, int32_t* status_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream,
+                           int reps, float* kernel_ms_host);
+
 #ifdef __cplusplus
 }
 #endif

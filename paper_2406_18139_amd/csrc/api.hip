@@ -196,4 +196,40 @@ int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* m
                                     st);
 }
 
+int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,
+                           int d, lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode,
+                           void* k_out, void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int reps, float* kernel_ms_host)
+{
+    if (reps <= 0 || kernel_ms_host == nullptr) return LOOKM_ERR_INVALID_ARG;
+    lookm_host::KernelTimer timer;
+    timer.st = (hipStream_t)hip_stream;
+    for (int i = 0; i <= LOOKM_N_KERNELS; ++i)
+        if (hipEventCreate(&timer.ev[i]) != hipSuccess) return LOOKM_ERR_DEVICE;
+    double sum[LOOKM_N_KERNELS] = {0};
+    int rc = LOOKM_OK;
+    for (int r = 0; r < reps && rc == LOOKM_OK; ++r) {
+        // a kernel that is skipped for these sizes leaves its event at the previous kernel's time
+        for (int i = 0; i <= LOOKM_N_KERNELS; ++i) (void)hipEventRecord(timer.ev[i], timer.st);
+        lookm_host::g_timer = &timer;
+        rc = lookm_compress(q, k, v, modality_mask, H, L, d, dt, budget, recent_window, merge_mode, k_out, v_out,
+                            kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
+        lookm_host::g_timer = nullptr;
+        if (hipStreamSynchronize(timer.st) != hipSuccess) rc = LOOKM_ERR_DEVICE;
+        float prev = 0.f;   // time since ev[0] of the latest kernel that actually ran
+        for (int i = 0; i < LOOKM_N_KERNELS && rc == LOOKM_OK; ++i) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, timer.ev[0], timer.ev[i + 1]) != hipSuccess) rc = LOOKM_ERR_DEVICE;
+            if (t > prev) { sum[i] += t - prev; prev = t; }
+        }
+    }
+    for (int i = 0; i <= LOOKM_N_KERNELS; ++i) (void)hipEventDestroy(timer.ev[i]);
+    for (int i = 0; i < LOOKM_N_KERNELS; ++i) kernel_ms_host[i] = (float)(sum[i] / reps);
+    return rc;
+}
+
 }  // extern "C"
+
+namespace lookm_host {
+thread_local KernelTimer* g_timer = nullptr;
+}

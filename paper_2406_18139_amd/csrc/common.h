@@ -86,4 +86,16 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }
 
+// Per-kernel timing for lookm_compress_profile: when a timer is installed, every launcher records an
+// event after each kernel it enqueues (ids follow the LOOKM_K_* order of the header).
+struct KernelTimer {
+    hipEvent_t ev[LOOKM_N_KERNELS + 1];
+    hipStream_t st;
+};
+extern thread_local KernelTimer* g_timer;
+inline void mark(int kernel_id)
+{
+    if (g_timer) (void)hipEventRecord(g_timer->ev[kernel_id + 1], g_timer->st);
+}
+
 }  // namespace lookm_host

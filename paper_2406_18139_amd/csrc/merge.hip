@@ -184,6 +184,7 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
         }
         hipLaunchKernelGGL(lookm::k_bucket, dim3(H), dim3(lookm::BK_THREADS), (size_t)W * B * sizeof(int), st, assign,
                            Le, B, W, nbits, offsets, members);
+        mark(LOOKM_K_BUCKET);
     }
     if (dt == LOOKM_BF16)
         launch_merge_t((const lookm::bf16_t*)k, (const lookm::bf16_t*)v, kept, evicted, sim, offsets, members, H, L, d,
@@ -191,6 +192,7 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
     else
         launch_merge_t((const float*)k, (const float*)v, kept, evicted, sim, offsets, members, H, L, d, B, mode,
                        (float*)k_out, (float*)v_out, st);
+    mark(LOOKM_K_MERGE);
     return hip_ok(hipGetLastError());
 }
 

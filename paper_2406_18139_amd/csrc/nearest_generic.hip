@@ -131,6 +131,7 @@ static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evic
     if (Le == 0) return LOOKM_OK;
     const size_t rows = (size_t)H * L;
     hipLaunchKernelGGL(lookm::k_rnorm<T>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, k, rows, d, rnorm);
+    mark(LOOKM_K_RNORM);
     if (mfma) return launch_nearest_mfma(k, kept, evicted, H, L, budget, rnorm, assign, sim, st);
     size_t lds = (size_t)2 * d * lookm::NT_TS * sizeof(float);
     if (lds < 8192) lds = 8192;
@@ -144,6 +145,7 @@ static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evic
     dim3 grid((Le + lookm::NT_TS - 1) / lookm::NT_TS, H);
     hipLaunchKernelGGL(lookm::k_nearest_generic<T>, grid, dim3(256), lds, st, k, rnorm, kept, evicted, L, d, budget,
                        Le, assign, sim);
+    mark(LOOKM_K_NEAREST);
     return hip_ok(hipGetLastError());
 }
 

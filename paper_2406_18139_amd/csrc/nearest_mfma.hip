@@ -120,6 +120,7 @@ int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evict
     const int tiles = (Le + lookm::NBS - 1) / lookm::NBS;
     hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3((unsigned)(tiles * H)), dim3(256), 0, st, (const lookm::bf16_t*)k,
                        rnorm, kept, evicted, H, L, budget, Le, assign, sim);
+    mark(LOOKM_K_NEAREST);
     return hip_ok(hipGetLastError());
 }
 

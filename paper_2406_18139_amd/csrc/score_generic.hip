@@ -176,7 +176,9 @@ static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, fl
         attr_done = true;
     }
     hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, L, d, scale2, lse);
+    mark(LOOKM_K_SCORE_LSE);
     hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, grid, block, lds, st, q, k, L, d, scale2, lse, scores);
+    mark(LOOKM_K_SCORE_COLSUM);
     return hip_ok(hipGetLastError());
 }
 

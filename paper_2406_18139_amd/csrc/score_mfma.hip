@@ -174,8 +174,10 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     dim3 grid((unsigned)(nS * H)), block(256);
     hipLaunchKernelGGL(lookm::k_score_mfma<1>, grid, block, 0, st, (const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H,
                        L, scale2, lse, scores);
+    mark(LOOKM_K_SCORE_LSE);
     hipLaunchKernelGGL(lookm::k_score_mfma<2>, grid, block, 0, st, (const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H,
                        L, scale2, lse, scores);
+    mark(LOOKM_K_SCORE_COLSUM);
     return hip_ok(hipGetLastError());
 }
 

@@ -158,6 +158,7 @@ int launch_select(const float* scores, const uint8_t* mask, int H, int L, int bu
 {
     hipLaunchKernelGGL(lookm::k_select, dim3(H), dim3(lookm::SEL_THREADS), 0, st, scores, mask, L, budget, M, kept,
                        evicted, status);
+    mark(LOOKM_K_SELECT);
     return hip_ok(hipGetLastError());
 }
 

@@ -29,7 +29,10 @@ MERGE_MODES = {"none": 0, "averaged": 1, "pivotal": 2, "weighted": 3}
 F32, BF16 = 0, 1
 
 EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
-           "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge"]
+           "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
+           "lookm_compress_profile"]
+
+KERNELS = ["score_lse", "score_colsum", "select", "rnorm", "nearest", "bucket", "merge"]   # LOOKM_K_* order
 
 
 class LookmError(RuntimeError):
@@ -59,6 +62,9 @@ def lib() -> ctypes.CDLL:
         L.lookm_workspace_bytes.argtypes = [I, I, I, I, I]
         L.lookm_compress.restype = I
         L.lookm_compress.argtypes = [vp, vp, vp, vp, I, I, I, I, I, I, I, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lookm_compress_profile.restype = I
+        L.lookm_compress_profile.argtypes = [vp, vp, vp, vp, I, I, I, I, I, I, I, vp, vp, vp, vp, vp, vp, sz, vp, I,
+                                             ctypes.POINTER(ctypes.c_float)]
         L.lookm_scores.restype = I
         L.lookm_scores.argtypes = [vp, vp, I, I, I, I, vp, vp, sz, vp]
         L.lookm_select.restype = I
@@ -148,12 +154,7 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
     B = int(budget)
     dev = q.device
     if out is None:
-        nb = max(B, 0)
-        out = Compressed(torch.empty((H, nb, d), dtype=q.dtype, device=dev),
-                         torch.empty((H, nb, d), dtype=q.dtype, device=dev),
-                         torch.empty((H, nb), dtype=torch.int32, device=dev),
-                         torch.empty((H, L), dtype=torch.float32, device=dev) if want_scores else None,
-                         torch.zeros(1, dtype=torch.int32, device=dev))
+        out = alloc_outputs(H, L, d, B, q.dtype, dev, want_scores)
     if workspace is None:
         workspace = alloc_workspace(H, L, d, min(max(B, 0), L), dt, dev)
     wp, wn = _ws_ptr(workspace)
@@ -169,6 +170,33 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
         if st != OK:
             raise LookmError(st, "lookm_compress (device)")
     return out
+
+
+def alloc_outputs(H: int, L: int, d: int, budget: int, dtype, device, want_scores: bool = False) -> Compressed:
+    nb = max(int(budget), 0)
+    return Compressed(torch.empty((H, nb, d), dtype=dtype, device=device),
+                      torch.empty((H, nb, d), dtype=dtype, device=device),
+                      torch.empty((H, nb), dtype=torch.int32, device=device),
+                      torch.empty((H, L), dtype=torch.float32, device=device) if want_scores else None,
+                      torch.zeros(1, dtype=torch.int32, device=device))
+
+
+def lookm_compress_profile(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode, reps: int,
+                           out: Compressed, workspace: torch.Tensor) -> dict:
+    """lookm_compress run ``reps`` times with an event after every kernel; returns {kernel: average ms}.
+    Synchronises the current stream."""
+    H, L, d = q.shape
+    wp, wn = _ws_ptr(workspace)
+    ms = (ctypes.c_float * len(KERNELS))()
+    rc = lib().lookm_compress_profile(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
+                                      H, L, d, _dt(q), int(budget), int(recent_window), _mode(merge_mode),
+                                      _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"),
+                                      _dev(out.kept_idx, "kept_idx"),
+                                      _dev(out.scores, "scores") if out.scores is not None else None,
+                                      _dev(out.status, "status"), wp, wn, _stream(), int(reps), ms)
+    if rc != OK:
+        raise LookmError(rc, "lookm_compress_profile")
+    return {name: float(ms[i]) for i, name in enumerate(KERNELS)}
 
 
 def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
