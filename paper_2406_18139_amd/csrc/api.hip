@@ -9,10 +9,10 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t lse, scores, evicted, assign, sim, rnorm, offsets, members, total;
+    size_t lse, scores, evicted, assign, sim, rnorm, offsets, members, partials, total;
 };
 
-Layout make_layout(int H, int L, int budget)
+Layout make_layout(int H, int L, int d, int dt, int budget)
 {
     const size_t HL = (size_t)H * L, HE = (size_t)H * (size_t)(L - budget);
     Layout w;
@@ -25,6 +25,7 @@ Layout make_layout(int H, int L, int budget)
     w.rnorm = o;   o += align_up(HL * sizeof(float));
     w.offsets = o; o += align_up((size_t)H * (budget + 1) * sizeof(int32_t));
     w.members = o; o += align_up(HE * sizeof(int32_t));
+    w.partials = o; o += align_up(lookm_host::scores_scratch_floats(H, L, d, (lookm_dtype)dt) * sizeof(float));
     w.total = o;
     return w;
 }
@@ -47,10 +48,10 @@ int check_budget(int L, int budget, int M)
     return LOOKM_OK;
 }
 
-int check_workspace(const void* ws, size_t bytes, int H, int L, int budget)
+int check_workspace(const void* ws, size_t bytes, int H, int L, int d, int dt, int budget)
 {
     if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return LOOKM_ERR_WORKSPACE;
-    if (bytes < make_layout(H, L, budget).total) return LOOKM_ERR_WORKSPACE;
+    if (bytes < make_layout(H, L, d, dt, budget).total) return LOOKM_ERR_WORKSPACE;
     return LOOKM_OK;
 }
 
@@ -88,7 +89,7 @@ int lookm_protected_count(const uint8_t* mask_host, int L, int recent_window)
 size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
 {
     if (check_shape(H, L, d, (int)dt) != LOOKM_OK || budget < 0 || budget > L) return 0;
-    return make_layout(H, L, budget).total;
+    return make_layout(H, L, d, (int)dt, budget).total;
 }
 
 int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
@@ -98,10 +99,11 @@ int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype 
     int rc = check_shape(H, L, d, (int)dt);
     if (rc != LOOKM_OK) return rc;
     if (!aligned16(q) || !aligned16(k) || !aligned16(scores_out)) return LOOKM_ERR_INVALID_ARG;
-    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
-        workspace_bytes < align_up((size_t)H * L * sizeof(float)))
-        return LOOKM_ERR_WORKSPACE;
-    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, 0), scores_out, (hipStream_t)hip_stream);
+    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, 0);
+    if (rc != LOOKM_OK) return rc;
+    const Layout w = make_layout(H, L, d, (int)dt, 0);
+    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores_out,
+                                     at<float>(workspace, w.partials), (hipStream_t)hip_stream);
 }
 
 int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L, int budget, int recent_window,
@@ -128,9 +130,9 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
     if (budget < 1 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
     if (budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;   // empty lists may be NULL
     if (!aligned16(k)) return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
-    const Layout w = make_layout(H, L, budget);
+    const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
                                       assign, sim, (hipStream_t)hip_stream);
 }
@@ -148,9 +150,9 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
     if (budget < 0 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
     if (merge_mode != LOOKM_MERGE_NONE && budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
-    const Layout w = make_layout(H, L, budget);
+    const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
                                     at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.members), k_out, v_out,
                                     (hipStream_t)hip_stream);
@@ -171,17 +173,18 @@ int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* m
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
         (scores_out && !aligned16(scores_out)))
         return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, budget);
+    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
 
-    const Layout w = make_layout(H, L, budget);
+    const Layout w = make_layout(H, L, d, (int)dt, budget);
     hipStream_t st = (hipStream_t)hip_stream;
     float* scores = scores_out ? scores_out : at<float>(workspace, w.scores);
     int32_t* evicted = at<int32_t>(workspace, w.evicted);
     int32_t* assign = at<int32_t>(workspace, w.assign);
     float* sim = at<float>(workspace, w.sim);
 
-    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores, st);
+    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores,
+                                   at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
     rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
     if (rc != LOOKM_OK) return rc;

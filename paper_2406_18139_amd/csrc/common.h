@@ -75,7 +75,8 @@ constexpr float kLog2e = 1.4426950408889634f;
 namespace lookm_host {
 
 int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, float* scores,
-                  hipStream_t st);
+                  float* scratch, hipStream_t st);
+size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st);
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,

@@ -156,7 +156,9 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
 
 namespace lookm_host {
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, hipStream_t st);
+int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, float* scratch,
+                       hipStream_t st);
+size_t scores_mfma_scratch_floats(int H, int L);
 
 template <typename T>
 static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, float* lse, float* scores, hipStream_t st)
@@ -182,11 +184,16 @@ static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, fl
     return hip_ok(hipGetLastError());
 }
 
+size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)
+{
+    return (dt == LOOKM_BF16 && d == 128) ? scores_mfma_scratch_floats(H, L) : 0;
+}
+
 int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, float* scores,
-                  hipStream_t st)
+                  float* scratch, hipStream_t st)
 {
     if (dt == LOOKM_BF16) {
-        if (d == 128) return launch_scores_mfma(q, k, H, L, d, lse, scores, st);
+        if (d == 128) return launch_scores_mfma(q, k, H, L, d, lse, scores, scratch, st);
         return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, L, d, lse, scores, st);
     }
     return launch_scores_generic((const float*)q, (const float*)k, H, L, d, lse, scores, st);

@@ -13,6 +13,9 @@
 // repeatable.  c = log2(e)/sqrt(d) folds the softmax scale into the exp2 argument.
 #include "common.h"
 
+#include <algorithm>
+#include <type_traits>
+
 namespace lookm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
@@ -25,18 +28,81 @@ constexpr int XSTRIDE = 136;   // LDS row stride in bf16 (272 B): 16-byte reads 
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
+// Epilogue of one finished 32x32 block: 16 accumulator entries of this lane = 16 streamed rows
+// against ONE stationary row.
+//   PASS 1: running (max, sum) of 2^(c*s) over the keys of the lane's query row.
+//   PASS 2: running sum of 2^(c*s - lse2_i) over the query rows of the lane's key; nl = -lse2_i of the
+//           16 streamed rows, read from LDS.
+template <int PASS, bool MASK>
+__device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb, int s, const float* nl,
+                                               float& m, float& l, float& run)
+{
+    if (PASS == 1) {
+        if (MASK) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (xb + 8 * (r >> 2) + (r & 3) > s) acc[r] = -INFINITY;   // key after the query
+        }
+        float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+        for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
+        bm = fmaxf(bm, acc[15]);
+        const float mn = fmaxf(m, bm * scale2);
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
+        l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
+        m = mn;
+    } else {
+        float sum = 0.f;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
+            const float nlv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float p = __builtin_amdgcn_exp2f(fmaf(acc[4 * g + e], scale2, nlv[e]));
+                if (MASK && (xb + 8 * g + e < s)) p = 0.f;   // query before the key
+                sum += p;
+            }
+        }
+        run += sum;
+    }
+}
+
+// ---- work decomposition -------------------------------------------------------------------------------
+// A strip is 256 stationary rows; its streamed range (keys 0..strip end in pass 1, query rows strip
+// start..L in pass 2) is 4..L/64 tiles long.  Strips are cut into chunks of at most C tiles, one
+// workgroup per chunk, so that no workgroup is much longer than the average (the longest strip alone
+// would otherwise set the kernel's duration).  Each chunk writes a partial result per stationary row;
+// a small second kernel folds a strip's chunks together in chunk order.
+__host__ __device__ inline int strip_tiles(int pass, int t, int L)
+{
+    const int rows = (pass == 1) ? min(L, (t + 1) * BS) : (L - t * BS);
+    return (rows + BX - 1) / BX;
+}
+__host__ __device__ inline int strip_chunks(int pass, int t, int L, int C) { return (strip_tiles(pass, t, L) + C - 1) / C; }
+
+// The matrix pipe and the vector ALU of a SIMD overlap ACROSS waves, not within one (measured: an MFMA
+// followed by independent VALU work in the same wave runs back to back), so the kernel keeps each
+// wave's code simple - MFMA chains, then the epilogue - and is sized for three resident waves per SIMD.
+//   PASS 1 writes part_a = running max, part_b = running sum (base-2 domain) per (chunk, stationary row).
+//   PASS 2 writes part_a = partial column sum per (chunk, stationary row).
 template <int PASS>
-__global__ void __launch_bounds__(256, 2)
-k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2,
-             float* __restrict__ lse2, float* __restrict__ scores)
+__global__ void __launch_bounds__(256, 3)
+k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2, int C, int U,
+             const float* __restrict__ lse2, float* __restrict__ part_a, float* __restrict__ part_b)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XSTRIDE];
-    __shared__ __attribute__((aligned(16))) float xl[2][BX];
+    __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
 
     const int h = blockIdx.x % H;      // heads interleave across consecutive workgroups (and so across XCDs)
-    const int t = blockIdx.x / H;
-    const int nS = (L + BS - 1) / BS;
-    const int tile = (PASS == 1) ? (nS - 1 - t) : t;   // longest strips first
+    const int u = blockIdx.x / H;      // chunk number within the head
+    int tile = 0, chunk = u;
+    for (int nc = strip_chunks(PASS, 0, L, C); chunk >= nc; nc = strip_chunks(PASS, tile, L, C)) {
+        chunk -= nc;
+        ++tile;
+    }
     const int s0 = tile * BS;
     const bf16_t* S = ((PASS == 1) ? q : k) + (size_t)h * L * SD;   // stationary tensor
     const bf16_t* X = ((PASS == 1) ? k : q) + (size_t)h * L * SD;   // streamed tensor
@@ -47,8 +113,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     // stationary fragments: lane holds row (w0 + cb*32 + n), dims ks*16 + half*8 .. +7
     bf16x8 sf[2][8];
+#pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const int row = w0 + cb * 32 + n;
+#pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
             if (row < L) v = *reinterpret_cast<const uint4*>(S + (size_t)row * SD + ks * 16 + half * 8);
@@ -56,109 +124,138 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         }
     }
 
-    const int x_begin = (PASS == 1) ? 0 : s0;
-    const int x_end = (PASS == 1) ? min(L, s0 + BS) : L;
+    const int strip_begin = (PASS == 1) ? 0 : s0;
+    const int strip_end = (PASS == 1) ? min(L, s0 + BS) : L;
+    const int x_begin = strip_begin + chunk * C * BX;
+    const int x_end = min(strip_end, x_begin + C * BX);
     const int n_it = (x_end - x_begin + BX - 1) / BX;
 
-    // staging: thread loads 4 chunks of 16 B: rows (tid/16) + 16*i, chunk tid%16
+    // staging: thread loads BX/16 chunks of 16 B: rows (tid/16) + 16*i, chunk tid%16
+    constexpr int NLD = BX / 16;
     const int ld_row = tid >> 4, ld_chunk = tid & 15;
-    uint4 stage[4];
+    uint4 stage[NLD];
     float stage_l = 0.f;
     auto load_tile = [&](int x0) {
-        for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
             const int row = x0 + ld_row + 16 * i;
             stage[i] = make_uint4(0, 0, 0, 0);
             if (row < L) stage[i] = *reinterpret_cast<const uint4*>(X + (size_t)row * SD + ld_chunk * 8);
         }
-        if (PASS == 2 && tid < BX) stage_l = (x0 + tid < L) ? lse_h[x0 + tid] : INFINITY;
+        if (PASS == 2 && tid < BX) stage_l = (x0 + tid < L) ? lse_h[x0 + tid] : INFINITY;   // negated at store time
     };
     auto store_tile = [&](int buf) {
-        for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int i = 0; i < NLD; ++i)
             *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 16 * i) * XSTRIDE + ld_chunk * 8]) = stage[i];
-        if (PASS == 2 && tid < BX) xl[buf][tid] = stage_l;
+        if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l;   // rows past the end: -inf, they contribute 0
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
-    float run[2] = {0.f, 0.f}, run_hi[2] = {0.f, 0.f};  // pass 2 state (two-level running sum)
+    float run[2] = {0.f, 0.f};                          // pass 2 state
+    const int sA = w0 + n, sB = w0 + 32 + n;            // stationary index of this lane for cb = 0, 1
 
     load_tile(x_begin);
     store_tile(0);
     __syncthreads();
 
-    for (int it = 0; it < n_it; ++it) {
+    // One tile.  MASK = true evaluates the causal condition per element and is correct for every tile;
+    // MASK = false is the same minus the comparisons, for tiles known to lie entirely inside the causal
+    // region.  Each variant gets a loop of its own below (one code path per loop).
+    auto tile_step = [&](auto mask_tag, int it) {
+        constexpr bool MASK = decltype(mask_tag)::value;
         const int buf = it & 1;
         const int x0 = x_begin + it * BX;
         if (it + 1 < n_it) load_tile(x0 + BX);
-
-        // wave-uniform tile classification against the causal boundary (query index >= key index)
-        const bool skip = (PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0);
-        const bool need_mask = (PASS == 1) ? (x0 + BX - 1 > w0) : (x0 < w0 + 63);
+        // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
+        const bool skip = MASK && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
         if (!skip) {
-            for (int rb = 0; rb < 2; ++rb) {
-                bf16x8 a[8];
+#pragma unroll 1   // one block of 32 streamed rows at a time keeps the kernel within 168 VGPRs
+            for (int rb = 0; rb < BX / 32; ++rb) {
                 const bf16_t* ap = &xs[buf][(rb * 32 + n) * XSTRIDE + half * 8];
+                bf16x8 a[8];
+#pragma unroll
                 for (int ks = 0; ks < 8; ++ks) a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + ks * 16));
-                float lrow[16];
-                if (PASS == 2) {
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 v = *reinterpret_cast<const float4*>(&xl[buf][rb * 32 + 8 * g + 4 * half]);
-                        lrow[4 * g + 0] = v.x; lrow[4 * g + 1] = v.y; lrow[4 * g + 2] = v.z; lrow[4 * g + 3] = v.w;
-                    }
+                f32x16 Xc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                f32x16 Yc = Xc;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
+                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
                 }
-                for (int cb = 0; cb < 2; ++cb) {
-                    f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    for (int ks = 0; ks < 8; ++ks)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[cb][ks], acc, 0, 0, 0);
-                    const int s = w0 + cb * 32 + n;                    // stationary index of this lane
-                    const int xb = x0 + rb * 32 + 4 * half;            // streamed index of element r: xb + 8*(r/4) + r%4
-                    if (PASS == 1) {
-                        float v[16];
-                        for (int r = 0; r < 16; ++r) v[r] = acc[r] * scale2;
-                        if (need_mask)
-                            for (int r = 0; r < 16; ++r)
-                                if (xb + 8 * (r >> 2) + (r & 3) > s) v[r] = -INFINITY;
-                        float bm = v[0];
-                        for (int r = 1; r < 16; ++r) bm = fmaxf(bm, v[r]);
-                        const float mn = fmaxf(m[cb], bm);
-                        float sum = 0.f;
-                        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(v[r] - mn);
-                        l[cb] = l[cb] * __builtin_amdgcn_exp2f(m[cb] - mn) + sum;
-                        m[cb] = mn;
-                    } else {
-                        float p[16];
-                        for (int r = 0; r < 16; ++r) p[r] = __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -lrow[r]));
-                        if (need_mask)
-                            for (int r = 0; r < 16; ++r)
-                                if (xb + 8 * (r >> 2) + (r & 3) < s) p[r] = 0.f;
-                        float sum = 0.f;
-                        for (int r = 0; r < 16; ++r) sum += p[r];
-                        run[cb] += sum;
-                    }
-                }
-            }
-            if (PASS == 2 && (it & 31) == 31) {
-                for (int cb = 0; cb < 2; ++cb) { run_hi[cb] += run[cb]; run[cb] = 0.f; }
+                const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
+                const float* nl = &xl[buf][rb * 32 + 4 * half];
+                block_epilogue<PASS, MASK>(Xc, scale2, xb, sA, nl, m[0], l[0], run[0]);
+                block_epilogue<PASS, MASK>(Yc, scale2, xb, sB, nl, m[1], l[1], run[1]);
             }
         }
         if (it + 1 < n_it) store_tile(buf ^ 1);
         __syncthreads();
+    };
+    using masked = std::integral_constant<bool, true>;
+    using plain = std::integral_constant<bool, false>;
+
+    if (PASS == 1) {
+        // keys stream upwards: tiles with x0 + BX - 1 <= w0 hold only keys at or before every query row
+        // of this wave; the tiles after them touch the diagonal
+        int n_plain = (w0 - x_begin + 1) / BX;        // largest count with x_begin + BX*count - 1 <= w0
+        n_plain = max(0, min(n_plain, n_it));
+        for (int it = 0; it < n_plain; ++it) tile_step(plain{}, it);
+        for (int it = n_plain; it < n_it; ++it) tile_step(masked{}, it);
+    } else {
+        // query rows stream upwards from the diagonal: tiles with x0 >= w0 + 63 need no mask
+        int n_masked = (w0 + 63 - x_begin + BX - 1) / BX;
+        n_masked = max(0, min(n_masked, n_it));
+        for (int it = 0; it < n_masked; ++it) tile_step(masked{}, it);
+        for (int it = n_masked; it < n_it; ++it) tile_step(plain{}, it);
     }
 
+    // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
+    // chunk's partial for rows 0..255 of the strip
+    float* pa = part_a + ((size_t)h * U + u) * BS;
+    float* pb = part_b + ((size_t)h * U + u) * BS;
+#pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        const int s = w0 + cb * 32 + n;
+        const int r = wave * 64 + cb * 32 + n;
         if (PASS == 1) {
             const float mo = __shfl_xor(m[cb], 32), lo = __shfl_xor(l[cb], 32);
             const float M = fmaxf(m[cb], mo);
-            // lower half first, so both lanes of a pair form the same sum
             const float la = half ? lo : l[cb], ma = half ? mo : m[cb];
             const float lb = half ? l[cb] : lo, mb = half ? m[cb] : mo;
             const float Ls = la * __builtin_amdgcn_exp2f(ma - M) + lb * __builtin_amdgcn_exp2f(mb - M);
-            if (half == 0 && s < L) lse2[(size_t)h * L + s] = M + log2f(Ls);
+            if (half == 0) { pa[r] = M; pb[r] = Ls; }
         } else {
-            const float tot = run_hi[cb] + run[cb];
-            const float other = __shfl_xor(tot, 32);
-            if (half == 0 && s < L) scores[(size_t)h * L + s] = tot + other;
+            const float other = __shfl_xor(run[cb], 32);
+            if (half == 0) pa[r] = half ? other + run[cb] : run[cb] + other;
         }
+    }
+}
+
+// Folds the chunks of every strip, in chunk order: pass 1 -> lse2[h, i] = log2 sum_j 2^(c q_i.k_j);
+// pass 2 -> scores[h, j] = A_s[j].  One thread per (head, row).
+template <int PASS>
+__global__ void __launch_bounds__(256)
+k_score_combine(int H, int L, int C, int U, const float* __restrict__ part_a, const float* __restrict__ part_b,
+                float* __restrict__ out)
+{
+    const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
+    const int row = tile * BS + r;
+    if (row >= L) return;
+    int u0 = 0;
+    for (int t = 0; t < tile; ++t) u0 += strip_chunks(PASS, t, L, C);
+    const int nc = strip_chunks(PASS, tile, L, C);
+    const float* pa = part_a + ((size_t)h * U + u0) * BS + r;
+    const float* pb = part_b + ((size_t)h * U + u0) * BS + r;
+    if (PASS == 1) {
+        float M = -1e30f;
+        for (int c = 0; c < nc; ++c) M = fmaxf(M, pa[(size_t)c * BS]);
+        float Ls = 0.f;
+        for (int c = 0; c < nc; ++c) Ls = fmaf(pb[(size_t)c * BS], exp2f(pa[(size_t)c * BS] - M), Ls);
+        out[(size_t)h * L + row] = M + log2f(Ls);
+    } else {
+        float sum = 0.f;
+        for (int c = 0; c < nc; ++c) sum += pa[(size_t)c * BS];
+        out[(size_t)h * L + row] = sum;
     }
 }
 
@@ -166,17 +263,55 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
 namespace lookm_host {
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, hipStream_t st)
+// tiles per chunk: aim at ~8 workgroups per resident slot (256 CUs x 3), at least 8 tiles per chunk
+static int chunk_tiles(int H, int L)
+{
+    long total = 0;
+    const int nS = (L + lookm::BS - 1) / lookm::BS;
+    for (int t = 0; t < nS; ++t) total += lookm::strip_tiles(2, t, L);
+#ifndef LOOKM_UNITS_TARGET
+#define LOOKM_UNITS_TARGET 6144
+#endif
+    long c = (total * H + LOOKM_UNITS_TARGET - 1) / LOOKM_UNITS_TARGET;
+    return (int)(c < 8 ? 8 : (c > 256 ? 256 : c));
+}
+
+static int total_chunks(int pass, int L, int C)
+{
+    const int nS = (L + lookm::BS - 1) / lookm::BS;
+    int u = 0;
+    for (int t = 0; t < nS; ++t) u += lookm::strip_chunks(pass, t, L, C);
+    return u;
+}
+
+// floats of scratch for the chunk partials (two arrays of U x 256 per head)
+size_t scores_mfma_scratch_floats(int H, int L)
+{
+    const int C = chunk_tiles(H, L);
+    const int U = std::max(total_chunks(1, L, C), total_chunks(2, L, C));
+    return (size_t)2 * H * U * lookm::BS;
+}
+
+int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, float* scratch,
+                       hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
+    const int C = chunk_tiles(H, L);
+    const int U1 = total_chunks(1, L, C), U2 = total_chunks(2, L, C);
+    const int Umax = std::max(U1, U2);
+    float* part_a = scratch;
+    float* part_b = scratch + (size_t)H * Umax * lookm::BS;
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
-    dim3 grid((unsigned)(nS * H)), block(256);
-    hipLaunchKernelGGL(lookm::k_score_mfma<1>, grid, block, 0, st, (const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H,
-                       L, scale2, lse, scores);
+    const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
+    const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
+    hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3((unsigned)(U1 * H)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U1,
+                       lse, part_a, part_b);
+    hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
     mark(LOOKM_K_SCORE_LSE);
-    hipLaunchKernelGGL(lookm::k_score_mfma<2>, grid, block, 0, st, (const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H,
-                       L, scale2, lse, scores);
+    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3((unsigned)(U2 * H)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
+                       lse, part_a, part_b);
+    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
     mark(LOOKM_K_SCORE_COLSUM);
     return hip_ok(hipGetLastError());
 }
