@@ -37,10 +37,13 @@ def algorithmic_work(w: W.Workload) -> dict:
     pairs = L * (L + 1) // 2
     return {
         "score_lse": ("mfma", 2.0 * d * pairs * H),
+        "score_lse_fold": ("hbm", H * 4.0 * L * 3),        # two partials in, one value out (at least one chunk)
         "score_colsum": ("mfma", 2.0 * d * pairs * H),
+        "score_colsum_fold": ("hbm", H * 4.0 * L * 2),
         "select": ("hbm", H * (4.0 * L + 4.0 * B + 4.0 * Le) + L),
         "rnorm": ("hbm", H * (L * d * e + 4.0 * L)),
         "nearest": ("mfma", 2.0 * d * Le * B * H),
+        "nearest_fold": ("hbm", H * (Le * (8.0 + 2 * d * e + 8.0 + 8.0))),   # partial in, two key rows, assign + sim out
         "bucket": ("hbm", H * (4.0 * Le + 4.0 * (B + 1) + 4.0 * Le)),
         "merge": ("hbm", H * (2.0 * L * d * e + 2.0 * B * d * e + 4.0 * B + 12.0 * Le + 4.0 * (B + 1))),
     }
@@ -53,6 +56,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", default="long", choices=["long", "long_total", "llava7b"])
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy kernel (to scale HBM byte counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -61,6 +66,16 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the compression path has no CPU fallback.", file=sys.stderr)
         return 2
+
+    if args.calibrate_copy:
+        n = 1 << 28                                       # 2^28 floats = 1 GiB read + 1 GiB written per copy
+        src = torch.arange(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n, "copies": 3}))
+        return 0
 
     w = {"long": W.LONG, "long_total": W.LONG_TOTAL, "llava7b": W.LLAVA7B}[args.workload]
     mode = w.modes[0]
@@ -103,12 +118,19 @@ def main() -> int:
     dbound, damount = work[dominant]
     dpeak = PEAK_MFMA_BF16 if dbound == "mfma" else PEAK_HBM
     dach = damount / (kms[dominant] * 1e-3)
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (scaled by the copy
+    # calibration); None when no summary covers this workload / kernel
+    traffic = None
+    tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic_{w.name}.json")
+    if os.path.exists(tfile):
+        with open(tfile) as f:
+            traffic = json.load(f).get("bytes_per_launch", {}).get(dominant)
     roofline = {"kernel": dominant, "bound": dbound,
                 "achieved": round(dach / (1e12 if dbound == "mfma" else 1e9), 3),
                 "peak": dpeak / (1e12 if dbound == "mfma" else 1e9),
                 "unit": "TFLOP/s" if dbound == "mfma" else "GB/s",
-                "frac": round(dach / dpeak, 4), "traffic": None}
-    score_ms = kms["score_lse"] + kms["score_colsum"]
+                "frac": round(dach / dpeak, 4), "traffic": traffic}
+    score_ms = kms["score_lse"] + kms["score_lse_fold"] + kms["score_colsum"] + kms["score_colsum_fold"]
     smc_ms = kms["select"] + kms["bucket"] + kms["merge"]
     smc_bytes = work["select"][1] + work["bucket"][1] + work["merge"][1]
     groups = {

@@ -145,7 +145,7 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
  * Eq. 10-12 + compaction: x_out[h, r] = merge of row kept_idx[h, r] of x with the rows
  * {evicted_idx[h, e] : assign[h, e] = r}, taken in ascending position, for x in {k, v}.
  *   assign  device, int32 [H, L - budget], values in [0, budget).   sim  device, float [H, L - budget]
- *   (read only by LOOKM_MERGE_WEIGHTED).
+ *   (used as weights by LOOKM_MERGE_WEIGHTED; must be a valid array for every merging mode).
  */
 int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int32_t* evicted_idx,
                 const int32_t* assign, const float* sim,
@@ -158,8 +158,10 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
 /* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;
  * Section 3.3: key norms, matching, similarity sets, merge + compaction). */
 enum {
-    LOOKM_K_SCORE_LSE = 0, LOOKM_K_SCORE_COLSUM = 1, LOOKM_K_SELECT = 2, LOOKM_K_RNORM = 3,
-    LOOKM_K_NEAREST = 4, LOOKM_K_BUCKET = 5, LOOKM_K_MERGE = 6, LOOKM_N_KERNELS = 7
+    LOOKM_K_SCORE_LSE = 0, LOOKM_K_SCORE_LSE_FOLD = 1,        /* pass 1 and the fold of its chunk partials */
+    LOOKM_K_SCORE_COLSUM = 2, LOOKM_K_SCORE_COLSUM_FOLD = 3,  /* pass 2 and the fold of its chunk partials */
+    LOOKM_K_SELECT = 4, LOOKM_K_RNORM = 5, LOOKM_K_NEAREST = 6, LOOKM_K_NEAREST_FOLD = 7,
+    LOOKM_K_BUCKET = 8, LOOKM_K_MERGE = 9, LOOKM_N_KERNELS = 10
 };
 
 /*

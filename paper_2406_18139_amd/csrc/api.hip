@@ -2,6 +2,8 @@
 // launch sequence of the compression path.  See include/lookm.h for the contract.
 #include "common.h"
 
+#include <algorithm>
+
 namespace {
 
 constexpr size_t kAlign = 256;
@@ -9,7 +11,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t lse, scores, evicted, assign, sim, rnorm, offsets, members, partials, total;
+    size_t lse, scores, evicted, assign, sim, rnorm, offsets, member_pos, member_w, partials, total;
 };
 
 Layout make_layout(int H, int L, int d, int dt, int budget)
@@ -24,8 +26,12 @@ Layout make_layout(int H, int L, int d, int dt, int budget)
     w.sim = o;     o += align_up(HE * sizeof(float));
     w.rnorm = o;   o += align_up(HL * sizeof(float));
     w.offsets = o; o += align_up((size_t)H * (budget + 1) * sizeof(int32_t));
-    w.members = o; o += align_up(HE * sizeof(int32_t));
-    w.partials = o; o += align_up(lookm_host::scores_scratch_floats(H, L, d, (lookm_dtype)dt) * sizeof(float));
+    w.member_pos = o; o += align_up(HE * sizeof(int32_t));
+    w.member_w = o;   o += align_up(HE * sizeof(float));
+    // the score partials and the matching partials are never live at the same time: one slice serves both
+    w.partials = o;
+    o += align_up(std::max(lookm_host::scores_scratch_floats(H, L, d, (lookm_dtype)dt) * sizeof(float),
+                           lookm_host::nearest_scratch_bytes(H, L, d, (lookm_dtype)dt, budget)));
     w.total = o;
     return w;
 }
@@ -134,7 +140,7 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
-                                      assign, sim, (hipStream_t)hip_stream);
+                                      assign, sim, at<void>(workspace, w.partials), (hipStream_t)hip_stream);
 }
 
 int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int32_t* evicted_idx,
@@ -154,8 +160,8 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
-                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.members), k_out, v_out,
-                                    (hipStream_t)hip_stream);
+                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.member_pos),
+                                    at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
 }
 
 int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L, int d,
@@ -191,12 +197,12 @@ int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* m
     if (merge_mode != LOOKM_MERGE_NONE && budget < L) {
         if (budget == 0) return LOOKM_OK;   // nothing conserved: nothing to merge into
         rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
-                                        assign, sim, st);
+                                        assign, sim, at<void>(workspace, w.partials), st);
         if (rc != LOOKM_OK) return rc;
     }
     return lookm_host::launch_merge(k, v, kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)merge_mode,
-                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.members), k_out, v_out,
-                                    st);
+                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.member_pos),
+                                    at<float>(workspace, w.member_w), k_out, v_out, st);
 }
 
 int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,

@@ -80,10 +80,11 @@ size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st);
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,
-                   int budget, float* rnorm, int32_t* assign, float* sim, hipStream_t st);
+                   int budget, float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st);
+size_t nearest_scratch_bytes(int H, int L, int d, lookm_dtype dt, int budget);
 int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_t* evicted, const int32_t* assign,
                  const float* sim, int H, int L, int d, lookm_dtype dt, int budget, int mode, int32_t* offsets,
-                 int32_t* members, void* k_out, void* v_out, hipStream_t st);
+                 int32_t* member_pos, float* member_w, void* k_out, void* v_out, hipStream_t st);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }
 

@@ -121,18 +121,19 @@ k_nearest_generic(const T* __restrict__ k, const float* __restrict__ rnorm, cons
 namespace lookm_host {
 
 int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int budget,
-                        const float* rnorm, int32_t* assign, float* sim, hipStream_t st);
+                        const float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st);
+size_t nearest_mfma_scratch_bytes(int H, int L, int B);
 
 template <typename T>
 static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, int budget,
-                            float* rnorm, int32_t* assign, float* sim, hipStream_t st, bool mfma)
+                            float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st, bool mfma)
 {
     const int Le = L - budget;
     if (Le == 0) return LOOKM_OK;
     const size_t rows = (size_t)H * L;
     hipLaunchKernelGGL(lookm::k_rnorm<T>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, k, rows, d, rnorm);
     mark(LOOKM_K_RNORM);
-    if (mfma) return launch_nearest_mfma(k, kept, evicted, H, L, budget, rnorm, assign, sim, st);
+    if (mfma) return launch_nearest_mfma(k, kept, evicted, H, L, budget, rnorm, assign, sim, scratch, st);
     size_t lds = (size_t)2 * d * lookm::NT_TS * sizeof(float);
     if (lds < 8192) lds = 8192;
     static bool attr_done = false;
@@ -149,13 +150,18 @@ static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evic
     return hip_ok(hipGetLastError());
 }
 
+size_t nearest_scratch_bytes(int H, int L, int d, lookm_dtype dt, int budget)
+{
+    return (dt == LOOKM_BF16 && d == 128) ? nearest_mfma_scratch_bytes(H, L, budget) : 0;
+}
+
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,
-                   int budget, float* rnorm, int32_t* assign, float* sim, hipStream_t st)
+                   int budget, float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st)
 {
     if (dt == LOOKM_BF16)
-        return launch_nearest_t((const lookm::bf16_t*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, st,
-                                d == 128);
-    return launch_nearest_t((const float*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, st, false);
+        return launch_nearest_t((const lookm::bf16_t*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, scratch,
+                                st, d == 128);
+    return launch_nearest_t((const float*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, scratch, st, false);
 }
 
 }  // namespace lookm_host

@@ -1,11 +1,25 @@
 // Nearest conserved key by cosine similarity (Section 3.3, Eq. 9) on the gfx950 matrix cores:
 // bf16 keys, head_dim 128.  Same machine as the score passes: a workgroup keeps the MFMA B-operand
 // fragments of 256 evicted keys (gathered through the evicted index list) in registers and streams
-// the conserved keys (gathered through the kept index list) past them in 64-row LDS tiles as the
-// A operand.  A lane's 16 accumulator values are 16 conserved slots against ONE evicted key, so the
-// running argmax is in-lane; the lane pair (lane, lane^32) is merged once after the loop.
-// The similarity matrix never exists in memory.  Ties go to the lower slot (= lower position).
+// conserved keys (gathered through the kept index list) past them in 64-row LDS tiles as the A operand.
+// A lane's 16 accumulator values are 16 conserved slots against ONE evicted key, so the running argmax
+// is in-lane; the lane pair (lane, lane^32) is merged once after the loop.  The similarity matrix never
+// exists in memory.
+//
+// Argmax without per-element compare/select chains: with y = (k_e.k_c)/||k_c|| = cos * ||k_e||, the value
+// t = ||k_e|| + y lies in [0, 2||k_e||], so its float bits order like signed integers (a t that rounding
+// pushed just below 0 is a negative integer and simply loses; ||k_e|| > 0 is common to the whole row);
+// the low 4 mantissa bits of each entry are replaced by 15 - r (r = entry number inside the 32x32
+// block), and one v_max3_i32 tree per block yields both the block maximum and where it sits.  Candidates are therefore compared at 20 mantissa bits (<= 1.9e-6 absolute); equal
+// keys still resolve to the lower slot exactly.  Across blocks, chunks and the lane pair the order is
+// (truncated value descending, slot ascending).  The `sim` output is decoded from the winning key.
+//
+// The conserved axis is cut into chunks (one workgroup per (evicted strip, chunk)) chosen so that the
+// number of workgroups fills the resident slots evenly; enumeration is chunk-major and XCD-affine as in
+// the score passes.
 #include "common.h"
+
+#include <algorithm>
 
 namespace lookm {
 
@@ -14,26 +28,51 @@ typedef __attribute__((ext_vector_type(16))) float nf32x16;
 
 constexpr int ND = 128, NBS = 256, NBX = 64, NXSTRIDE = 136;
 
-__global__ void __launch_bounds__(256, 2)
+// partial result of one (evicted strip, chunk): key = float bits of t >> 4, slot
+struct NearestPartial {
+    int32_t key;
+    int32_t slot;
+};
+
+__global__ void __launch_bounds__(256, 3)
 k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
-               const int32_t* __restrict__ evicted, int H, int L, int B, int Le, int32_t* __restrict__ assign,
-               float* __restrict__ sim)
+               const int32_t* __restrict__ evicted, int H, int L, int B, int Le, int n_strips, int n_chunks, int CT,
+               NearestPartial* __restrict__ part)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][NBX * NXSTRIDE];
     __shared__ __attribute__((aligned(16))) float xr[2][NBX];
 
-    const int h = blockIdx.x % H, tile = blockIdx.x / H;
+    // XCD-affine enumeration (see k_score_mfma): units of a head are chunk-major
+    const int U = n_strips * n_chunks;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    int h, e;
+    if (H >= 8) {
+        h = (j / U) * 8 + xcd;
+        e = j % U;
+    } else {
+        const int xph = 8 / H;
+        h = xcd / xph;
+        e = j * xph + xcd % xph;
+    }
+    if (h >= H || e >= U) return;
+    const int chunk = e / n_strips, strip = e % n_strips;
+
     k += (size_t)h * L * ND;
     rnorm += (size_t)h * L;
     kept += (size_t)h * B;
     evicted += (size_t)h * Le;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, n = lane & 31;
-    const int w0 = tile * NBS + wave * 64;   // first evicted-list index of this wave
+    const int w0 = strip * NBS + wave * 64;   // first evicted-list index of this wave
 
     nbf16x8 sf[2][8];
+    float off[2];    // ||k_e|| of this lane's two evicted keys (0 for a zero key)
+#pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        const int e = w0 + cb * 32 + n;
-        const bf16_t* row = (e < Le) ? k + (size_t)evicted[e] * ND : nullptr;
+        const int ev = w0 + cb * 32 + n;
+        const bf16_t* row = (ev < Le) ? k + (size_t)evicted[ev] * ND : nullptr;
+        const float rne = (ev < Le) ? rnorm[evicted[ev]] : 0.f;
+        off[cb] = (rne > 0.f) ? 1.0f / rne : 0.f;
+#pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
             if (row) v = *reinterpret_cast<const uint4*>(row + ks * 16 + half * 8);
@@ -41,86 +80,194 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         }
     }
 
-    const int n_it = (B + NBX - 1) / NBX;
+    const int x_begin = chunk * CT, x_end = min(B, x_begin + CT);
+    const int n_it = (x_end - x_begin + NBX - 1) / NBX;
     const int ld_row = tid >> 4, ld_chunk = tid & 15;
-    uint4 stage[4];
+    // Staging registers are plain scalars (an array captured by the helpers ended up in scratch memory).
+    // Slots past the end of the conserved list are staged as copies of the last conserved key: they tie
+    // with it and lose on the slot rule.  The gather is two dependent loads (position, then row); the
+    // positions are fetched one tile ahead of the rows so that neither wait is exposed.
+    uint4 st0, st1, st2, st3;
     float stage_r = 0.f;
-    auto load_tile = [&](int x0) {
-        for (int i = 0; i < 4; ++i) {
-            const int slot = x0 + ld_row + 16 * i;
-            stage[i] = make_uint4(0, 0, 0, 0);
-            if (slot < B) stage[i] = *reinterpret_cast<const uint4*>(k + (size_t)kept[slot] * ND + ld_chunk * 8);
-        }
-        if (tid < NBX) stage_r = (x0 + tid < B) ? rnorm[kept[x0 + tid]] : 0.f;
-    };
-    auto store_tile = [&](int buf) {
-        for (int i = 0; i < 4; ++i)
-            *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 16 * i) * NXSTRIDE + ld_chunk * 8]) = stage[i];
-        if (tid < NBX) xr[buf][tid] = stage_r;
-    };
+    int ix0, ix1, ix2, ix3, ridx = 0;
+#define LOOKM_LOAD_INDEX(x0)                                   \
+    do {                                                       \
+        ix0 = kept[min((x0) + ld_row, B - 1)];                 \
+        ix1 = kept[min((x0) + ld_row + 16, B - 1)];            \
+        ix2 = kept[min((x0) + ld_row + 32, B - 1)];            \
+        ix3 = kept[min((x0) + ld_row + 48, B - 1)];            \
+        if (tid < NBX) ridx = kept[min((x0) + tid, B - 1)];    \
+    } while (0)
+#define LOOKM_LOAD_TILE()                                                                      \
+    do {                                                                                       \
+        st0 = *reinterpret_cast<const uint4*>(k + (size_t)ix0 * ND + ld_chunk * 8);            \
+        st1 = *reinterpret_cast<const uint4*>(k + (size_t)ix1 * ND + ld_chunk * 8);            \
+        st2 = *reinterpret_cast<const uint4*>(k + (size_t)ix2 * ND + ld_chunk * 8);            \
+        st3 = *reinterpret_cast<const uint4*>(k + (size_t)ix3 * ND + ld_chunk * 8);            \
+        if (tid < NBX) stage_r = rnorm[ridx];                                                  \
+    } while (0)
+#define LOOKM_STORE_TILE(buf)                                                                  \
+    do {                                                                                       \
+        *reinterpret_cast<uint4*>(&xs[buf][(ld_row)*NXSTRIDE + ld_chunk * 8]) = st0;           \
+        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 16) * NXSTRIDE + ld_chunk * 8]) = st1;    \
+        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 32) * NXSTRIDE + ld_chunk * 8]) = st2;    \
+        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 48) * NXSTRIDE + ld_chunk * 8]) = st3;    \
+        if (tid < NBX) xr[buf][tid] = stage_r;                                                 \
+    } while (0)
 
-    float bv[2] = {-INFINITY, -INFINITY};
-    int bs[2] = {0x7fffffff, 0x7fffffff};
+    // per stationary row of this lane; the initial state decodes to slot 0 with t = 0 (= cosine -1)
+    int bhi[2] = {0, 0};            // best truncated key (>> 4)
+    int bkey[2] = {15, 15};         // its full key (low 4 bits: 15 - entry number)
+    int bxb[2] = {0, 0};            // slot of entry 0 of the block it came from
 
-    load_tile(0);
-    store_tile(0);
+    LOOKM_LOAD_INDEX(x_begin);
+    LOOKM_LOAD_TILE();
+    LOOKM_LOAD_INDEX(x_begin + NBX);     // clamped, so always in range
+    LOOKM_STORE_TILE(0);
     __syncthreads();
     for (int it = 0; it < n_it; ++it) {
-        const int buf = it & 1, x0 = it * NBX;
-        if (it + 1 < n_it) load_tile(x0 + NBX);
-        const bool tail = x0 + NBX > B;
+        const int buf = it & 1, x0 = x_begin + it * NBX;
+        if (it + 1 < n_it) {
+            LOOKM_LOAD_TILE();                   // rows of tile it+1 (positions fetched one iteration ago)
+            LOOKM_LOAD_INDEX(x0 + 2 * NBX);      // positions of tile it+2
+        }
+#pragma unroll 1
         for (int rb = 0; rb < 2; ++rb) {
             nbf16x8 a[8];
             const bf16_t* ap = &xs[buf][(rb * 32 + n) * NXSTRIDE + half * 8];
+#pragma unroll
             for (int ks = 0; ks < 8; ++ks) a[ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + ks * 16));
-            float rn[16];
-            for (int g = 0; g < 4; ++g) {
-                const float4 v = *reinterpret_cast<const float4*>(&xr[buf][rb * 32 + 8 * g + 4 * half]);
-                rn[4 * g + 0] = v.x; rn[4 * g + 1] = v.y; rn[4 * g + 2] = v.z; rn[4 * g + 3] = v.w;
+            nf32x16 acc[2];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], acc[1], 0, 0, 0);
             }
-            const int xb = x0 + rb * 32 + 4 * half;   // slot of element r: xb + 8*(r/4) + r%4 (ascending in r)
+            const int xb = x0 + rb * 32 + 4 * half;   // slot of entry r: xb + 8*(r/4) + r%4
+            const float* rp = &xr[buf][rb * 32 + 4 * half];
+#pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
-                nf32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                for (int ks = 0; ks < 8; ++ks)
-                    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[cb][ks], acc, 0, 0, 0);
-                for (int r = 0; r < 16; ++r) {
-                    const int slot = xb + 8 * (r >> 2) + (r & 3);
-                    float v = acc[r] * rn[r];
-                    if (tail && slot >= B) v = -INFINITY;
-                    if (v > bv[cb]) { bv[cb] = v; bs[cb] = slot; }
+                int u[16];
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 rv = *reinterpret_cast<const float4*>(rp + 8 * g);
+                    const float rn[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int r = 4 * g + i;
+                        // ||k_e|| + (k_e.k_c) * rnorm_c (a zero evicted key gives 0 everywhere: slot 0 wins)
+                        const float t = fmaf(acc[cb][r], rn[i], off[cb]);
+                        u[r] = (int)((__float_as_uint(t) & 0xfffffff0u) | (uint32_t)(15 - r));
+                    }
                 }
+                int bm = max(max(u[0], u[1]), u[2]);
+#pragma unroll
+                for (int r = 3; r < 15; r += 2) bm = max(max(bm, u[r]), u[r + 1]);
+                bm = max(bm, u[15]);
+                const int hi = bm >> 4;
+                const bool better = hi > bhi[cb];   // strict: an equal value in a later block loses
+                bhi[cb] = better ? hi : bhi[cb];
+                bkey[cb] = better ? bm : bkey[cb];
+                bxb[cb] = better ? xb : bxb[cb];
             }
         }
-        if (it + 1 < n_it) store_tile(buf ^ 1);
+        if (it + 1 < n_it) LOOKM_STORE_TILE(buf ^ 1);
         __syncthreads();
     }
+#undef LOOKM_LOAD_INDEX
+#undef LOOKM_LOAD_TILE
+#undef LOOKM_STORE_TILE
 
+    NearestPartial* out = part + (((size_t)h * n_chunks + chunk) * n_strips + strip) * NBS;
+#pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        const float ov = __shfl_xor(bv[cb], 32);
-        const int os = __shfl_xor(bs[cb], 32);
-        float v = bv[cb];
-        int s = bs[cb];
-        if (ov > v || (ov == v && os < s)) { v = ov; s = os; }
-        const int e = w0 + cb * 32 + n;
-        if (half == 0 && e < Le) {
-            assign[(size_t)h * Le + e] = s;
-            sim[(size_t)h * Le + e] = v * rnorm[evicted[e]];
+        const int r = 15 - (bkey[cb] & 15);
+        int slot = bxb[cb] + 8 * (r >> 2) + (r & 3);
+        int hi = bhi[cb];
+        const int ohi = __shfl_xor(hi, 32);
+        const int oslot = __shfl_xor(slot, 32);
+        if (ohi > hi || (ohi == hi && oslot < slot)) { hi = ohi; slot = oslot; }
+        if (half == 0) {
+            NearestPartial p;
+            p.key = hi;
+            p.slot = slot;
+            out[wave * 64 + cb * 32 + n] = p;
         }
     }
+}
+
+// Folds the chunks of every evicted key (value descending, slot ascending): assign[h, e] = slot and
+// sim[h, e] = cosine, decoded from the winning key at the centre of its truncation interval
+// (|error| <= 1e-6).  One thread per evicted key.
+__global__ void __launch_bounds__(256)
+k_nearest_fold(const float* __restrict__ rnorm, const int32_t* __restrict__ evicted, int L, int B, int Le,
+               int n_strips, int n_chunks, const NearestPartial* __restrict__ part, int32_t* __restrict__ assign,
+               float* __restrict__ sim)
+{
+    const int h = blockIdx.y;
+    const int ev = blockIdx.x * 256 + threadIdx.x;
+    if (ev >= Le) return;
+    const int strip = ev / NBS, r = ev % NBS;
+    int bk = -1, bs = 0x7fffffff;
+    for (int c = 0; c < n_chunks; ++c) {
+        const NearestPartial p = part[(((size_t)h * n_chunks + c) * n_strips + strip) * NBS + r];
+        if (p.key > bk || (p.key == bk && p.slot < bs)) { bk = p.key; bs = p.slot; }
+    }
+    const float rne = rnorm[(size_t)h * L + evicted[(size_t)h * Le + ev]];
+    const float off = (rne > 0.f) ? 1.0f / rne : 0.f;
+    const float t = __uint_as_float(((uint32_t)max(bk, 0) << 4) | 8u);     // ||k_e|| + (k_e.k_c) * rnorm_c
+    assign[(size_t)h * Le + ev] = min(max(bs, 0), B - 1);
+    sim[(size_t)h * Le + ev] = (rne > 0.f) ? (t - off) * rne : 0.f;
 }
 
 }  // namespace lookm
 
 namespace lookm_host {
 
-int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int budget,
-                        const float* rnorm, int32_t* assign, float* sim, hipStream_t st)
+// chunks of the conserved axis: the count (at most 8, at least 4 tiles each) whose workgroup total fills
+// the resident slots (256 CUs x 3) most evenly
+static int nearest_chunks(int H, int Le, int B)
 {
-    const int Le = L - budget;
-    const int tiles = (Le + lookm::NBS - 1) / lookm::NBS;
-    hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3((unsigned)(tiles * H)), dim3(256), 0, st, (const lookm::bf16_t*)k,
-                       rnorm, kept, evicted, H, L, budget, Le, assign, sim);
+    const int strips = (Le + lookm::NBS - 1) / lookm::NBS, tiles = (B + lookm::NBX - 1) / lookm::NBX;
+    int best = 1;
+    double best_eff = 0.0;
+    for (int c = 1; c <= 8 && (c == 1 || tiles / c >= 4); ++c) {
+        const long units = (long)strips * c * H;
+        const double eff = (double)units / (double)(((units + 767) / 768) * 768);
+        if (eff > best_eff + 0.02) { best_eff = eff; best = c; }
+    }
+    return best;
+}
+
+size_t nearest_mfma_scratch_bytes(int H, int L, int B)
+{
+    const int Le = L - B;
+    if (Le <= 0 || B <= 0) return 0;
+    const int strips = (Le + lookm::NBS - 1) / lookm::NBS;
+    return (size_t)H * 8 * strips * lookm::NBS * sizeof(lookm::NearestPartial);
+}
+
+int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int budget,
+                        const float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st)
+{
+    const int B = budget, Le = L - B;
+    const int strips = (Le + lookm::NBS - 1) / lookm::NBS, tiles = (B + lookm::NBX - 1) / lookm::NBX;
+    const int nc = nearest_chunks(H, Le, B);
+    const int CT = ((tiles + nc - 1) / nc) * lookm::NBX;        // conserved slots per chunk
+    const int n_chunks = (B + CT - 1) / CT;
+    const int U = strips * n_chunks;
+    unsigned grid;
+    if (H >= 8) grid = 8u * (unsigned)((H + 7) / 8) * (unsigned)U;
+    else { const int xph = 8 / H; grid = 8u * (unsigned)((U + xph - 1) / xph); }
+    lookm::NearestPartial* part = (lookm::NearestPartial*)scratch;
+    hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3(grid), dim3(256), 0, st, (const lookm::bf16_t*)k, rnorm, kept,
+                       evicted, H, L, B, Le, strips, n_chunks, CT, part);
     mark(LOOKM_K_NEAREST);
+    hipLaunchKernelGGL(lookm::k_nearest_fold, dim3((Le + 255) / 256, H), dim3(256), 0, st, rnorm, evicted, L, B, Le,
+                       strips, n_chunks, part, assign, sim);
+    mark(LOOKM_K_NEAREST_FOLD);
     return hip_ok(hipGetLastError());
 }
 

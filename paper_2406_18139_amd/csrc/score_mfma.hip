@@ -72,16 +72,18 @@ __device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb,
 
 // ---- work decomposition -------------------------------------------------------------------------------
 // A strip is 256 stationary rows; its streamed range (keys 0..strip end in pass 1, query rows strip
-// start..L in pass 2) is 4..L/64 tiles long.  Strips are cut into chunks of at most C tiles, one
-// workgroup per chunk, so that no workgroup is much longer than the average (the longest strip alone
-// would otherwise set the kernel's duration).  Each chunk writes a partial result per stationary row;
-// a small second kernel folds a strip's chunks together in chunk order.
-__host__ __device__ inline int strip_tiles(int pass, int t, int L)
+// start..L in pass 2) is 4..L/64 tiles long.  The streamed axis is cut at multiples of CT = C*64 rows
+// into chunks, one workgroup per (strip, chunk), so that no workgroup is much longer than the average
+// (the longest strip alone would otherwise set the kernel's duration).  Chunk boundaries are the same
+// for every strip, and work is enumerated chunk-major, so the workgroups resident on an XCD at one
+// time stream the SAME rows of the same head and share them in that XCD's L2.  Each workgroup writes a
+// partial result per stationary row; a small second kernel folds a strip's chunks together in order.
+__host__ __device__ inline int first_chunk(int pass, int t, int CT) { return (pass == 1) ? 0 : (t * BS) / CT; }
+__host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT)
 {
-    const int rows = (pass == 1) ? min(L, (t + 1) * BS) : (L - t * BS);
-    return (rows + BX - 1) / BX;
+    if (pass == 1) return (min(L, (t + 1) * BS) + CT - 1) / CT;
+    return (L + CT - 1) / CT - (t * BS) / CT;
 }
-__host__ __device__ inline int strip_chunks(int pass, int t, int L, int C) { return (strip_tiles(pass, t, L) + C - 1) / C; }
 
 // The matrix pipe and the vector ALU of a SIMD overlap ACROSS waves, not within one (measured: an MFMA
 // followed by independent VALU work in the same wave runs back to back), so the kernel keeps each
@@ -96,14 +98,31 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XSTRIDE];
     __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
 
-    const int h = blockIdx.x % H;      // heads interleave across consecutive workgroups (and so across XCDs)
-    const int u = blockIdx.x / H;      // chunk number within the head
-    int tile = 0, chunk = u;
-    for (int nc = strip_chunks(PASS, 0, L, C); chunk >= nc; nc = strip_chunks(PASS, tile, L, C)) {
-        chunk -= nc;
-        ++tile;
+    // Consecutive workgroup ids go to consecutive XCDs.  With 8 or more heads, XCD x works through heads
+    // x, x+8, ... one at a time, so its L2 holds one head's current chunk; with fewer heads each head
+    // gets 8/H XCDs that share its units round-robin.
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    int h, e;
+    if (H >= 8) {
+        h = (j / U) * 8 + xcd;
+        e = j % U;
+    } else {
+        const int xph = 8 / H;            // XCDs per head
+        h = xcd / xph;
+        e = j * xph + xcd % xph;
+    }
+    if (h >= H || e >= U) return;
+    const int nS = (L + BS - 1) / BS, CT = C * BX;
+    int g = 0, tile = 0;
+    for (;; ++g) {      // chunk-major enumeration: all strips that touch chunk g, then chunk g+1, ...
+        const int t_first = (PASS == 1) ? (g * CT) / BS : 0;
+        const int cnt = (PASS == 1) ? nS - t_first : min(nS, ((g + 1) * CT + BS - 1) / BS);
+        if (e < cnt) { tile = t_first + e; break; }
+        e -= cnt;
     }
     const int s0 = tile * BS;
+    int u = g - first_chunk(PASS, tile, CT);   // slot of this chunk in the strip-major partial arrays
+    for (int t = 0; t < tile; ++t) u += strip_chunks(PASS, t, L, CT);
     const bf16_t* S = ((PASS == 1) ? q : k) + (size_t)h * L * SD;   // stationary tensor
     const bf16_t* X = ((PASS == 1) ? k : q) + (size_t)h * L * SD;   // streamed tensor
     const float* lse_h = lse2 + (size_t)h * L;
@@ -126,8 +145,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     const int strip_begin = (PASS == 1) ? 0 : s0;
     const int strip_end = (PASS == 1) ? min(L, s0 + BS) : L;
-    const int x_begin = strip_begin + chunk * C * BX;
-    const int x_end = min(strip_end, x_begin + C * BX);
+    const int x_begin = max(strip_begin, g * CT);
+    const int x_end = min(strip_end, (g + 1) * CT);
     const int n_it = (x_end - x_begin + BX - 1) / BX;
 
     // staging: thread loads BX/16 chunks of 16 B: rows (tid/16) + 16*i, chunk tid%16
@@ -241,9 +260,10 @@ k_score_combine(int H, int L, int C, int U, const float* __restrict__ part_a, co
     const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
     const int row = tile * BS + r;
     if (row >= L) return;
+    const int CT = C * BX;
     int u0 = 0;
-    for (int t = 0; t < tile; ++t) u0 += strip_chunks(PASS, t, L, C);
-    const int nc = strip_chunks(PASS, tile, L, C);
+    for (int t = 0; t < tile; ++t) u0 += strip_chunks(PASS, t, L, CT);
+    const int nc = strip_chunks(PASS, tile, L, CT);
     const float* pa = part_a + ((size_t)h * U + u0) * BS + r;
     const float* pb = part_b + ((size_t)h * U + u0) * BS + r;
     if (PASS == 1) {
@@ -268,7 +288,7 @@ static int chunk_tiles(int H, int L)
 {
     long total = 0;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
-    for (int t = 0; t < nS; ++t) total += lookm::strip_tiles(2, t, L);
+    for (int t = 0; t < nS; ++t) total += (L - t * lookm::BS + lookm::BX - 1) / lookm::BX;
 #ifndef LOOKM_UNITS_TARGET
 #define LOOKM_UNITS_TARGET 6144
 #endif
@@ -280,8 +300,16 @@ static int total_chunks(int pass, int L, int C)
 {
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     int u = 0;
-    for (int t = 0; t < nS; ++t) u += lookm::strip_chunks(pass, t, L, C);
+    for (int t = 0; t < nS; ++t) u += lookm::strip_chunks(pass, t, L, C * lookm::BX);
     return u;
+}
+
+// workgroups of one score pass: 8 XCD lanes x (units per lane), see the mapping at the top of k_score_mfma
+static unsigned score_grid(int H, int U)
+{
+    if (H >= 8) return 8u * (unsigned)((H + 7) / 8) * (unsigned)U;
+    const int xph = 8 / H;
+    return 8u * (unsigned)((U + xph - 1) / xph);
 }
 
 // floats of scratch for the chunk partials (two arrays of U x 256 per head)
@@ -305,14 +333,16 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
-    hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3((unsigned)(U1 * H)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U1,
+    hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U1,
                        lse, part_a, part_b);
-    hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
     mark(LOOKM_K_SCORE_LSE);
-    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3((unsigned)(U2 * H)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
+    hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
+    mark(LOOKM_K_SCORE_LSE_FOLD);
+    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
                        lse, part_a, part_b);
-    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
     mark(LOOKM_K_SCORE_COLSUM);
+    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
+    mark(LOOKM_K_SCORE_COLSUM_FOLD);
     return hip_ok(hipGetLastError());
 }
 

@@ -32,7 +32,8 @@ EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "loo
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile"]
 
-KERNELS = ["score_lse", "score_colsum", "select", "rnorm", "nearest", "bucket", "merge"]   # LOOKM_K_* order
+KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
+           "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
 
 
 class LookmError(RuntimeError):

@@ -67,7 +67,7 @@ def check_nearest(k_head_f32: np.ndarray, kept, evicted, assign_gpu, sim_gpu):
         c = (ki @ kj) / (np.sqrt(ki @ ki) * np.sqrt(kj @ kj))
         assert s_ref[e] - c <= TIE_COS, f"evicted {evicted[e]}: kernel chose cos {c:.7f}, best is {s_ref[e]:.7f}"
     ok = a_ref == assign_gpu
-    np.testing.assert_allclose(sim_gpu[ok], s_ref[ok], rtol=0, atol=2e-6)
+    np.testing.assert_allclose(sim_gpu[ok], s_ref[ok], rtol=0, atol=4e-6)
     return int(bad.size)
 
 
@@ -104,7 +104,8 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None):
     np.testing.assert_allclose(scores_g.astype(np.float64).sum(1), L, rtol=2e-5)
 
     oh = list(range(H)) if oracle_heads is None else list(oracle_heads)
-    stats = dict(heads_checked=len(oh), kept_diff_heads=0, nearest_tie_rows=0, score_relerr=0.0, merge_abserr=0.0)
+    stats = dict(heads_checked=len(oh), kept_diff_heads=0, nearest_tie_rows=0, rows_matched=len(oh) * max(L - B, 0),
+                 score_relerr=0.0, merge_abserr=0.0)
     if mode == "none" or B == L:
         evg = None
     # stage outputs of the same kernels, for the matching / merging checks
