@@ -43,7 +43,7 @@ def algorithmic_work(w: W.Workload) -> dict:
         "select": ("hbm", H * (4.0 * L + 4.0 * B + 4.0 * Le) + L),
         "rnorm": ("hbm", H * (L * d * e + 4.0 * L)),
         "nearest": ("mfma", 2.0 * d * Le * B * H),
-        "nearest_fold": ("hbm", H * (Le * (8.0 + 2 * d * e + 8.0 + 8.0))),   # partial in, two key rows, assign + sim out
+        "nearest_fold": ("hbm", H * (Le * (8.0 + 4.0 + 4.0 + 4.0 + 4.0))),   # one partial, position, norm in; assign + sim out
         "bucket": ("hbm", H * (4.0 * Le + 4.0 * (B + 1) + 4.0 * Le)),
         "merge": ("hbm", H * (2.0 * L * d * e + 2.0 * B * d * e + 4.0 * B + 12.0 * Le + 4.0 * (B + 1))),
     }

@@ -121,8 +121,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         e -= cnt;
     }
     const int s0 = tile * BS;
-    int u = g - first_chunk(PASS, tile, CT);   // slot of this chunk in the strip-major partial arrays
-    for (int t = 0; t < tile; ++t) u += strip_chunks(PASS, t, L, CT);
+    const int n_chunks_total = (L + CT - 1) / CT;
+    const int u = g * nS + tile;               // slot of this (chunk, strip) in the partial arrays [h][chunk][strip][256]
     const bf16_t* S = ((PASS == 1) ? q : k) + (size_t)h * L * SD;   // stationary tensor
     const bf16_t* X = ((PASS == 1) ? k : q) + (size_t)h * L * SD;   // streamed tensor
     const float* lse_h = lse2 + (size_t)h * L;
@@ -231,8 +231,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
     // chunk's partial for rows 0..255 of the strip
-    float* pa = part_a + ((size_t)h * U + u) * BS;
-    float* pb = part_b + ((size_t)h * U + u) * BS;
+    float* pa = part_a + ((size_t)h * n_chunks_total * nS + u) * BS;
+    float* pb = part_b + ((size_t)h * n_chunks_total * nS + u) * BS;
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const int r = wave * 64 + cb * 32 + n;
@@ -260,21 +260,20 @@ k_score_combine(int H, int L, int C, int U, const float* __restrict__ part_a, co
     const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
     const int row = tile * BS + r;
     if (row >= L) return;
-    const int CT = C * BX;
-    int u0 = 0;
-    for (int t = 0; t < tile; ++t) u0 += strip_chunks(PASS, t, L, CT);
-    const int nc = strip_chunks(PASS, tile, L, CT);
-    const float* pa = part_a + ((size_t)h * U + u0) * BS + r;
-    const float* pb = part_b + ((size_t)h * U + u0) * BS + r;
+    const int CT = C * BX, nS = gridDim.x, G = (L + CT - 1) / CT;
+    const int g0 = first_chunk(PASS, tile, CT), nc = strip_chunks(PASS, tile, L, CT);
+    const size_t stride = (size_t)nS * BS;      // from one chunk of a strip to the next
+    const float* pa = part_a + (((size_t)h * G + g0) * nS + tile) * BS + r;
+    const float* pb = part_b + (((size_t)h * G + g0) * nS + tile) * BS + r;
     if (PASS == 1) {
         float M = -1e30f;
-        for (int c = 0; c < nc; ++c) M = fmaxf(M, pa[(size_t)c * BS]);
+        for (int c = 0; c < nc; ++c) M = fmaxf(M, pa[c * stride]);
         float Ls = 0.f;
-        for (int c = 0; c < nc; ++c) Ls = fmaf(pb[(size_t)c * BS], exp2f(pa[(size_t)c * BS] - M), Ls);
+        for (int c = 0; c < nc; ++c) Ls = fmaf(pb[c * stride], exp2f(pa[c * stride] - M), Ls);
         out[(size_t)h * L + row] = M + log2f(Ls);
     } else {
         float sum = 0.f;
-        for (int c = 0; c < nc; ++c) sum += pa[(size_t)c * BS];
+        for (int c = 0; c < nc; ++c) sum += pa[c * stride];
         out[(size_t)h * L + row] = sum;
     }
 }
@@ -312,12 +311,12 @@ static unsigned score_grid(int H, int U)
     return 8u * (unsigned)((U + xph - 1) / xph);
 }
 
-// floats of scratch for the chunk partials (two arrays of U x 256 per head)
+// floats of scratch for the chunk partials: two arrays [H][chunks][strips][256]
 size_t scores_mfma_scratch_floats(int H, int L)
 {
-    const int C = chunk_tiles(H, L);
-    const int U = std::max(total_chunks(1, L, C), total_chunks(2, L, C));
-    return (size_t)2 * H * U * lookm::BS;
+    const int C = chunk_tiles(H, L), CT = C * lookm::BX;
+    const int nS = (L + lookm::BS - 1) / lookm::BS, G = (L + CT - 1) / CT;
+    return (size_t)2 * H * G * nS * lookm::BS;
 }
 
 int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, float* scratch,
@@ -327,9 +326,9 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     const int C = chunk_tiles(H, L);
     const int U1 = total_chunks(1, L, C), U2 = total_chunks(2, L, C);
-    const int Umax = std::max(U1, U2);
+    const int G = (L + C * lookm::BX - 1) / (C * lookm::BX);
     float* part_a = scratch;
-    float* part_b = scratch + (size_t)H * Umax * lookm::BS;
+    float* part_b = scratch + (size_t)H * G * nS * lookm::BS;
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;

@@ -5,14 +5,17 @@
 // window with the highest accumulated score.  Eq. 5's "add max(A_s) to text scores" only serves to
 // rank every text token above every image token, so it is realised as a class, not as a float add.
 // The k_img-th largest score is found by an MSB-first radix select over the monotone integer image
-// of the float bits (4 passes of 8 bits, LDS histograms); equal scores are resolved towards the
+// of the float bits (digits of 12, 12 and 8 bits, LDS histograms); equal scores are resolved towards the
 // lower position by an ordered prefix count.  Kept and evicted index lists come out ascending.
+// Supports L <= 32 * 1024 (32 positions per thread).
 #include "common.h"
 
 namespace lookm {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_BINS = 4096;    // 12-bit digits
+constexpr int SEL_CAND = 4096;    // capacity of the LDS candidate list
 
 // order-preserving map float -> uint32 (larger float <=> larger key); -0 is folded onto +0
 __device__ __forceinline__ uint32_t score_key(float s)
@@ -22,15 +25,15 @@ __device__ __forceinline__ uint32_t score_key(float s)
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// exclusive prefix count of a predicate over the workgroup, in thread order; total returned via ref.
-// Uses two barriers; `wtot` is a 16-entry LDS array reserved for this helper.
-__device__ __forceinline__ int block_prefix_count(bool pred, int* wtot, int& total)
+// exclusive prefix sum over the workgroup's 16 waves of one wave-uniform int, and the total.  Two barriers;
+// `wtot` is a 16-entry LDS array reserved for this helper.
+__device__ __forceinline__ int wave_scan_excl(int wave_value, int* wtot, int& total)
 {
-    const uint64_t b = __ballot(pred);
     const int wave = threadIdx.x >> 6;
-    if (lane_id() == 0) wtot[wave] = __popcll(b);
+    if (lane_id() == 0) wtot[wave] = wave_value;
     __syncthreads();
     int before = 0, tot = 0;
+#pragma unroll
     for (int w = 0; w < SEL_WAVES; ++w) {
         const int c = wtot[w];
         before += (w < wave) ? c : 0;
@@ -38,31 +41,51 @@ __device__ __forceinline__ int block_prefix_count(bool pred, int* wtot, int& tot
     }
     __syncthreads();
     total = tot;
-    return before + mask_rank(b);
+    return before;
 }
 
+// Wave w owns the contiguous segment [w*64*IPT, (w+1)*64*IPT) of positions; inside it lane l holds
+// positions seg + i*64 + l, i < IPT, so global reads and writes are coalesced.  Keys and classes are
+// read once and stay in registers for the radix passes and the compaction; ordered counts are ballots
+// inside the wave plus one 16-entry scan across waves.
+template <int IPT>
 __global__ void __launch_bounds__(SEL_THREADS)
 k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int L, int B, int M,
          int32_t* __restrict__ kept, int32_t* __restrict__ evicted, int32_t* __restrict__ status)
 {
-    __shared__ int hist[256];
+    __shared__ int hist[SEL_BINS];
+    __shared__ uint32_t cand[SEL_CAND];     // keys that share the threshold's top 12 bits
     __shared__ int wtot[SEL_WAVES];
-    __shared__ int sh_bin, sh_k;
+    __shared__ int sh_bin, sh_k, sh_ncand;
 
-    const int h = blockIdx.x, tid = threadIdx.x;
+    const int h = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     scores += (size_t)h * L;
     kept += (size_t)h * B;
     evicted += (size_t)h * (L - B);
     const int head_len = L - M;   // positions [0, head_len) are outside the recent window
+    const int seg = wave * 64 * IPT;
 
-    // |T u R|
-    int nprot = 0;
-    for (int c0 = 0; c0 < L; c0 += SEL_THREADS) {
-        const int j = c0 + tid;
-        int tot;
-        block_prefix_count(j < L && (mask[j] == 0 || j >= head_len), wtot, tot);
-        nprot += tot;
+    uint32_t key[IPT];
+    uint32_t prot_m = 0, evic_m = 0;   // bit i: position seg + i*64 + lane is protected / evictable
+    int nprot_wave = 0;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int j = seg + i * 64 + lane;
+        key[i] = 0;
+        bool prot = false;
+        if (j < L) {
+            prot = (mask[j] == 0 || j >= head_len);
+            if (prot) prot_m |= 1u << i;
+            else {
+                evic_m |= 1u << i;
+                key[i] = score_key(scores[j]);
+            }
+        }
+        nprot_wave += __popcll(__ballot(prot));
     }
+
+    int nprot;   // |T u R|
+    wave_scan_excl(nprot_wave, wtot, nprot);
     const int k_img = B - nprot;
     if (k_img < 0) {
         // text + window do not fit: report, and leave in-range (meaningless) index lists behind
@@ -75,77 +98,124 @@ k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int
     const int n_evictable = L - nprot;
     const bool keep_all = (k_img == n_evictable), keep_none = (k_img == 0);
 
-    // radix select: key of the k_img-th largest evictable score, and how many equal keys to take
+    // Radix select, MSB first in digits of 12, 12 and 8 bits: key of the k_img-th largest evictable score
+    // and how many keys equal to it to take.  After the first digit the few surviving keys are copied to
+    // an LDS list, so the later digits cost one pass over that list instead of one over all positions
+    // (if more than SEL_CAND keys share their top 12 bits, the later digits re-read the registers).
     uint32_t thr = 0;
     int need_eq = 0;
     if (!keep_all && !keep_none) {
-        uint32_t prefix = 0;
         int kk = k_img;
-        for (int pass = 0; pass < 4; ++pass) {
-            const int shift = 24 - 8 * pass;
-            if (tid < 256) hist[tid] = 0;
-            __syncthreads();
-            for (int j = tid; j < head_len; j += SEL_THREADS) {
-                if (mask[j] == 0) continue;
-                const uint32_t key = score_key(scores[j]);
-                if (pass == 0 || (key >> (shift + 8)) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        // finds the bin (counting from the top) where the running count first reaches kk; every thread
+        // owns SEL_BINS / SEL_THREADS consecutive bins in descending order
+        auto find_bin = [&](int nbins) {
+            const int per = (nbins + SEL_THREADS - 1) / SEL_THREADS;   // 4 or 1
+            int c[4] = {0, 0, 0, 0}, sum = 0;
+            for (int i = 0; i < per; ++i) {
+                const int bin = nbins - 1 - (tid * per + i);
+                c[i] = (bin >= 0) ? hist[bin] : 0;
+                sum += c[i];
+            }
+            int incl = sum;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_up(incl, off);
+                if (lane >= off) incl += v;
+            }
+            int tot;
+            int cum = wave_scan_excl(__shfl(incl, 63), wtot, tot) + incl - sum;   // count in bins above mine
+            for (int i = 0; i < per; ++i) {
+                if (cum < kk && cum + c[i] >= kk) { sh_bin = nbins - 1 - (tid * per + i); sh_k = kk - cum; }
+                cum += c[i];
             }
             __syncthreads();
-            if (tid < 64) {
-                // wave 0: lane i owns bins 255-4i .. 252-4i (descending); find the bin where the
-                // running count from the top first reaches kk
-                int c[4], sum = 0;
-                for (int i = 0; i < 4; ++i) { c[i] = hist[255 - 4 * tid - i]; sum += c[i]; }
-                int incl = sum;
-                for (int off = 1; off < 64; off <<= 1) {
-                    const int v = __shfl_up(incl, off);
-                    if (tid >= off) incl += v;
-                }
-                int cum = incl - sum;   // count in bins above this lane's bins
-                for (int i = 0; i < 4; ++i) {
-                    if (cum < kk && cum + c[i] >= kk) { sh_bin = 255 - 4 * tid - i; sh_k = kk - cum; }
-                    cum += c[i];
-                }
-            }
-            __syncthreads();
-            prefix = (prefix << 8) | (uint32_t)sh_bin;
             kk = sh_k;
-            __syncthreads();
+            return (uint32_t)sh_bin;
+        };
+
+        for (int i = tid; i < SEL_BINS; i += SEL_THREADS) hist[i] = 0;
+        if (tid == 0) sh_ncand = 0;
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < IPT; ++i)
+            if ((evic_m >> i) & 1u) atomicAdd(&hist[key[i] >> 20], 1);
+        __syncthreads();
+        const uint32_t d0 = find_bin(SEL_BINS);
+        const int n_cand = hist[d0];
+        const bool listed = n_cand <= SEL_CAND;
+        __syncthreads();
+        for (int i = tid; i < SEL_BINS; i += SEL_THREADS) hist[i] = 0;
+        if (listed) {
+#pragma unroll
+            for (int i = 0; i < IPT; ++i)
+                if (((evic_m >> i) & 1u) && (key[i] >> 20) == d0) cand[atomicAdd(&sh_ncand, 1)] = key[i];
         }
-        thr = prefix;
+        __syncthreads();
+        if (listed) {
+            for (int c = tid; c < n_cand; c += SEL_THREADS) atomicAdd(&hist[(cand[c] >> 8) & 0xfffu], 1);
+        } else {
+#pragma unroll
+            for (int i = 0; i < IPT; ++i)
+                if (((evic_m >> i) & 1u) && (key[i] >> 20) == d0) atomicAdd(&hist[(key[i] >> 8) & 0xfffu], 1);
+        }
+        __syncthreads();
+        const uint32_t d1 = find_bin(SEL_BINS);
+        const uint32_t top24 = (d0 << 12) | d1;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        if (listed) {
+            for (int c = tid; c < n_cand; c += SEL_THREADS)
+                if ((cand[c] >> 8) == top24) atomicAdd(&hist[cand[c] & 0xffu], 1);
+        } else {
+#pragma unroll
+            for (int i = 0; i < IPT; ++i)
+                if (((evic_m >> i) & 1u) && (key[i] >> 8) == top24) atomicAdd(&hist[key[i] & 0xffu], 1);
+        }
+        __syncthreads();
+        const uint32_t d2 = find_bin(256);
+        thr = (top24 << 8) | d2;
         need_eq = kk;
     }
 
-    // ordered compaction
-    int kept_base = 0, ev_base = 0, eq_base = 0;
-    for (int c0 = 0; c0 < L; c0 += SEL_THREADS) {
-        const int j = c0 + tid;
-        const bool valid = j < L;
-        bool prot = false, evictable = false;
-        uint32_t key = 0;
+    // ordered compaction.  First the equal keys: those at the lowest positions fill what is left.
+    uint32_t keep_m = prot_m, eq_m = 0;
+    int eq_wave = 0;
+    if (keep_all) keep_m |= evic_m;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        bool eq = false;
+        if (!keep_all && !keep_none && ((evic_m >> i) & 1u)) {
+            if (key[i] > thr) keep_m |= 1u << i;
+            else if (key[i] == thr) { eq = true; eq_m |= 1u << i; }
+        }
+        eq_wave += __popcll(__ballot(eq));
+    }
+    int eq_tot;
+    int eq_run = wave_scan_excl(eq_wave, wtot, eq_tot);   // equal keys in lower waves
+    int keep_wave = 0;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const bool eq = (eq_m >> i) & 1u;
+        const uint64_t eb = __ballot(eq);
+        if (eq && eq_run + mask_rank(eb) < need_eq) keep_m |= 1u << i;
+        eq_run += __popcll(eb);
+        keep_wave += __popcll(__ballot((keep_m >> i) & 1u));
+    }
+    int keep_tot;
+    int kp = wave_scan_excl(keep_wave, wtot, keep_tot);   // kept positions in lower waves
+    int ep = min(seg, L) - kp;                             // evicted positions in lower waves
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int j = seg + i * 64 + lane;
+        const bool valid = j < L, keep = (keep_m >> i) & 1u;
+        const uint64_t kb = __ballot(valid && keep), vb = __ballot(valid);
         if (valid) {
-            prot = (mask[j] == 0) || (j >= head_len);
-            evictable = !prot;
-            if (evictable) key = score_key(scores[j]);
+            const int r = mask_rank(kb);
+            if (keep) kept[kp + r] = j;
+            else evicted[ep + lane - r] = j;               // valid lanes are a prefix of the wave
         }
-        bool keep = prot;
-        if (evictable) {
-            if (keep_all) keep = true;
-            else if (!keep_none) keep = key > thr;
-        }
-        const bool is_eq = evictable && !keep_all && !keep_none && key == thr;
-        int eq_tot;
-        const int eq_rank = eq_base + block_prefix_count(is_eq, wtot, eq_tot);
-        eq_base += eq_tot;
-        if (is_eq && eq_rank < need_eq) keep = true;
-        int keep_tot;
-        const int kp = block_prefix_count(keep, wtot, keep_tot);
-        if (valid) {
-            if (keep) kept[kept_base + kp] = j;
-            else evicted[ev_base + (tid - kp)] = j;
-        }
-        kept_base += keep_tot;
-        ev_base += min(SEL_THREADS, L - c0) - keep_tot;
+        kp += __popcll(kb);
+        ep += __popcll(vb) - __popcll(kb);
     }
 }
 
@@ -156,8 +226,18 @@ namespace lookm_host {
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st)
 {
-    hipLaunchKernelGGL(lookm::k_select, dim3(H), dim3(lookm::SEL_THREADS), 0, st, scores, mask, L, budget, M, kept,
-                       evicted, status);
+    const int per_thread = (L + lookm::SEL_THREADS - 1) / lookm::SEL_THREADS;
+    dim3 grid(H), block(lookm::SEL_THREADS);
+    if (per_thread <= 4)
+        hipLaunchKernelGGL(lookm::k_select<4>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+    else if (per_thread <= 8)
+        hipLaunchKernelGGL(lookm::k_select<8>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+    else if (per_thread <= 16)
+        hipLaunchKernelGGL(lookm::k_select<16>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+    else if (per_thread <= 32)
+        hipLaunchKernelGGL(lookm::k_select<32>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+    else
+        return LOOKM_ERR_UNSUPPORTED;
     mark(LOOKM_K_SELECT);
     return hip_ok(hipGetLastError());
 }
