@@ -24,7 +24,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int SD = 128;        // head dim
 constexpr int BS = 256;        // stationary rows per workgroup
 constexpr int BX = 64;         // streamed rows per iteration
-constexpr int XSTRIDE = 136;   // LDS row stride in bf16 (272 B): 16-byte reads of 8 consecutive rows hit all banks once
+constexpr int XROW = 128;       // LDS row = 256 B, unpadded; the 16-byte chunk c of row r sits at chunk c ^ (r & 7),
+                               // so 16-byte reads of 8 consecutive rows at the same c hit all 32 banks once
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
@@ -95,7 +96,7 @@ __global__ void __launch_bounds__(256, 3)
 k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2, int C, int U,
              const float* __restrict__ lse2, float* __restrict__ part_a, float* __restrict__ part_b)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XSTRIDE];
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
 
     // Consecutive workgroup ids go to consecutive XCDs.  With 8 or more heads, XCD x works through heads
@@ -149,24 +150,26 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     const int x_end = min(strip_end, (g + 1) * CT);
     const int n_it = (x_end - x_begin + BX - 1) / BX;
 
-    // staging: thread loads BX/16 chunks of 16 B: rows (tid/16) + 16*i, chunk tid%16
-    constexpr int NLD = BX / 16;
-    const int ld_row = tid >> 4, ld_chunk = tid & 15;
-    uint4 stage[NLD];
+    // Staging goes from global memory straight into LDS (global_load_lds_dwordx4): the 64 lanes of a wave
+    // fill 1 KB = 4 consecutive LDS rows, lane l landing at chunk l%16 of row l/16, so the swizzle is applied
+    // on the global side: the lane fetches chunk (l%16) ^ (row & 7) of its row.  Rows past the end re-read the
+    // last row (their contribution is masked out or weighted by 2^-inf).  No staging registers, no LDS stores.
+    constexpr int NLD = BX / 16;   // 1 KB pieces per wave and tile
+    const int ld_sub = lane >> 4, ld_pos = lane & 15;
     float stage_l = 0.f;
-    auto load_tile = [&](int x0) {
+    auto load_tile = [&](int x0, int buf) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-            const int row = x0 + ld_row + 16 * i;
-            stage[i] = make_uint4(0, 0, 0, 0);
-            if (row < L) stage[i] = *reinterpret_cast<const uint4*>(X + (size_t)row * SD + ld_chunk * 8);
+            const int row = (i * 4 + wave) * 4 + ld_sub;                        // row inside the tile
+            const int grow = min(x0 + row, L - 1);
+            const bf16_t* src = X + (size_t)grow * SD + ((ld_pos ^ (row & 7)) * 8);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW],
+                                             16, 0, 0);
         }
         if (PASS == 2 && tid < BX) stage_l = (x0 + tid < L) ? lse_h[x0 + tid] : INFINITY;   // negated at store time
     };
     auto store_tile = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i)
-            *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 16 * i) * XSTRIDE + ld_chunk * 8]) = stage[i];
         if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l;   // rows past the end: -inf, they contribute 0
     };
 
@@ -174,8 +177,9 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     float run[2] = {0.f, 0.f};                          // pass 2 state
     const int sA = w0 + n, sB = w0 + 32 + n;            // stationary index of this lane for cb = 0, 1
 
-    load_tile(x_begin);
+    load_tile(x_begin, 0);
     store_tile(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
     // One tile.  MASK = true evaluates the causal condition per element and is correct for every tile;
@@ -185,16 +189,17 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         constexpr bool MASK = decltype(mask_tag)::value;
         const int buf = it & 1;
         const int x0 = x_begin + it * BX;
-        if (it + 1 < n_it) load_tile(x0 + BX);
+        if (it + 1 < n_it) load_tile(x0 + BX, buf ^ 1);
         // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
         const bool skip = MASK && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
         if (!skip) {
 #pragma unroll 1   // one block of 32 streamed rows at a time keeps the kernel within 168 VGPRs
             for (int rb = 0; rb < BX / 32; ++rb) {
-                const bf16_t* ap = &xs[buf][(rb * 32 + n) * XSTRIDE + half * 8];
+                const bf16_t* ap = &xs[buf][(rb * 32 + n) * XROW];
                 bf16x8 a[8];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + ks * 16));
+                for (int ks = 0; ks < 8; ++ks)
+                    a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + (((2 * ks + half) ^ (n & 7)) * 8)));
                 f32x16 Xc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 f32x16 Yc = Xc;
 #pragma unroll
@@ -209,6 +214,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             }
         }
         if (it + 1 < n_it) store_tile(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the next tile's direct-to-LDS loads have landed
         __syncthreads();
     };
     using masked = std::integral_constant<bool, true>;

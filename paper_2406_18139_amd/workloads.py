@@ -105,6 +105,28 @@ def generate(w: Workload, layer: int = 0, heads: Sequence[int] | None = None):
     return to(q), to(k), to(v), torch.from_numpy(mask)
 
 
+def generate_on_device(w: Workload, layer: int = 0, device="cuda:0"):
+    """Same recipe as ``generate`` but drawn with a seeded torch generator on the GPU (different values, same
+    distribution): for timing many layers without minutes of host-side random number generation.  Not used
+    for parity (the oracle is fed from ``generate``)."""
+    g = torch.Generator(device=device)
+    g.manual_seed(w.seed(layer))
+    L, d, H = w.L, w.d, w.H
+    mask = torch.from_numpy(w.mask()).to(device)
+    img = mask == 1
+    n_image_tok = int(img.sum())
+    cluster = torch.randint(0, w.C, (n_image_tok,), generator=g, device=device)
+    q = torch.randn((H, L, d), generator=g, device=device)
+    k = torch.randn((H, L, d), generator=g, device=device)
+    v = torch.randn((H, L, d), generator=g, device=device)
+    ck = torch.randn((H, w.C, d), generator=g, device=device)
+    cv = torch.randn((H, w.C, d), generator=g, device=device)
+    k[:, img] = ck[:, cluster] + w.sigma * k[:, img]
+    v[:, img] = cv[:, cluster] + w.sigma * v[:, img]
+    dt = w.torch_dtype()
+    return q.to(dt), k.to(dt), v.to(dt), mask
+
+
 _SP4 = (64, 16, 32, 48, 128, 24, 40, 56, 80, 16, 96, 32, 64, 20, 112, 28, 36, 44, 72, 52, 64)
 
 TINY = Workload("tiny", 1, 2, 64, "f32", (32, 32, 64), 64, 8, 0.1, 0.20, 16,
