@@ -153,6 +153,27 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
                 void* k_out, void* v_out,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- reuse of the prefill's row log-sum-exp ------------------------------------------------------------ */
+
+/*
+ * A flash-style prefill attention kernel already holds, for every query row i, the natural-log
+ * log-sum-exp of its scaled causal logits, row_lse[h, i] = log sum_{j<=i} exp(q_i.k_j/sqrt(d)) - the
+ * normaliser of the attention weights A_p of Eq. 4.  Handing it over skips the first of the two score
+ * passes (half of the path's matrix work).  The values must belong to the same q, k (an inconsistent
+ * row_lse scales that row's contribution to every score).
+ *   row_lse  device, float [H, L].  Everything else as in lookm_scores / lookm_compress.
+ */
+int lookm_scores_lse(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
+                     float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                       const float* row_lse,
+                       int H, int L, int d, lookm_dtype dt,
+                       int budget, int recent_window, lookm_merge_mode merge_mode,
+                       void* k_out, void* v_out, int32_t* kept_idx,
+                       float* scores_out, int32_t* status_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- measurement aid ------------------------------------------------------------------------------- */
 
 /* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;

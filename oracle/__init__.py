@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_scores_head.restype = None
         L.oracle_scores.argtypes = [fp, fp, I, I, I, dp]
         L.oracle_scores.restype = None
+        L.oracle_row_lse.argtypes = [fp, fp, I, I, I, dp]
+        L.oracle_row_lse.restype = None
         L.oracle_protected_count.argtypes = [up, I, I]
         L.oracle_protected_count.restype = I
         L.oracle_select_head.argtypes = [dp, up, I, I, I, ip, ip]
@@ -111,6 +113,19 @@ def scores(q, k) -> np.ndarray:
     H, L, d = q.shape
     out = np.empty((H, L), dtype=np.float64)
     lib().oracle_scores(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, _p(out, ctypes.c_double))
+    return out[0] if single else out
+
+
+def row_lse(q, k) -> np.ndarray:
+    """Natural-log log-sum-exp of every causal row of q k^T / sqrt(d) (the normaliser of A_p in Eq. 4).
+    q, k: [H, L, d] (or [L, d]) -> float64 [H, L] (or [L])."""
+    q, k = as_f32(q), as_f32(k)
+    single = q.ndim == 2
+    if single:
+        q, k = q[None], k[None]
+    H, L, d = q.shape
+    out = np.empty((H, L), dtype=np.float64)
+    lib().oracle_row_lse(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, _p(out, ctypes.c_double))
     return out[0] if single else out
 
 

@@ -77,6 +77,29 @@ void oracle_scores_head(const float *q, const float *k, int L, int d, double *sc
     free(s);
 }
 
+/* Natural-log log-sum-exp of every row of the causal scaled logits, lse[i] = log sum_{j<=i} exp(q_i.k_j/sqrt(d)):
+ * the normaliser of A_p in Eq. 4 (A_p[i, j] = exp(s_ij - lse[i])), which a prefill attention kernel already holds. */
+void oracle_row_lse_head(const float *q, const float *k, int L, int d, double *lse)
+{
+    double *t = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
+    const double inv_root_d = 1.0 / sqrt((double)d);
+    for (int i = 0; i < L; ++i) {
+        const float *qi = q + (size_t)i * d;
+        double top = -INFINITY;
+        for (int j = 0; j <= i; ++j) {           /* causal: keys 0..i */
+            const float *kj = k + (size_t)j * d;
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += (double)qi[c] * (double)kj[c];
+            t[j] = acc * inv_root_d;
+            if (t[j] > top) top = t[j];
+        }
+        double z = 0.0;
+        for (int j = 0; j <= i; ++j) z += exp(t[j] - top);
+        lse[i] = top + log(z);
+    }
+    free(t);
+}
+
 /* ---- Eq. 5-8: text-prior selection of one head ---------------------------------------- */
 typedef struct { double key; int32_t pos; } cand_t;
 
@@ -248,6 +271,13 @@ void oracle_scores(const float *q, const float *k, int H, int L, int d, double *
 }
 
 /* threads the all-heads entry points will use */
+void oracle_row_lse(const float *q, const float *k, int H, int L, int d, double *lse)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h)
+        oracle_row_lse_head(q + (size_t)h * L * d, k + (size_t)h * L * d, L, d, lse + (size_t)h * L);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

@@ -98,8 +98,8 @@ size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
     return make_layout(H, L, d, (int)dt, budget).total;
 }
 
-int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
-                 void* workspace, size_t workspace_bytes, void* hip_stream)
+static int scores_impl(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
+                       float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!q || !k || !scores_out) return LOOKM_ERR_INVALID_ARG;
     int rc = check_shape(H, L, d, (int)dt);
@@ -108,8 +108,21 @@ int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype 
     rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, 0);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, 0);
-    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores_out,
+    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores_out,
                                      at<float>(workspace, w.partials), (hipStream_t)hip_stream);
+}
+
+int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
+                 void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return scores_impl(q, k, nullptr, H, L, d, dt, scores_out, workspace, workspace_bytes, hip_stream);
+}
+
+int lookm_scores_lse(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
+                     float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!row_lse) return LOOKM_ERR_INVALID_ARG;
+    return scores_impl(q, k, row_lse, H, L, d, dt, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L, int budget, int recent_window,
@@ -164,10 +177,10 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
                                     at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
 }
 
-int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L, int d,
-                   lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode, void* k_out,
-                   void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out, void* workspace,
-                   size_t workspace_bytes, void* hip_stream)
+static int compress_impl(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                         const float* row_lse, int H, int L, int d, lookm_dtype dt, int budget, int recent_window,
+                         lookm_merge_mode merge_mode, void* k_out, void* v_out, int32_t* kept_idx, float* scores_out,
+                         int32_t* status_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!q || !k || !v || !modality_mask || !status_out) return LOOKM_ERR_INVALID_ARG;
     if (budget > 0 && (!k_out || !v_out || !kept_idx)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
@@ -189,7 +202,7 @@ int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* m
     int32_t* assign = at<int32_t>(workspace, w.assign);
     float* sim = at<float>(workspace, w.sim);
 
-    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), scores,
+    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores,
                                    at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
     rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
@@ -203,6 +216,25 @@ int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* m
     return lookm_host::launch_merge(k, v, kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)merge_mode,
                                     at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), k_out, v_out, st);
+}
+
+int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L, int d,
+                   lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode, void* k_out,
+                   void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out, void* workspace,
+                   size_t workspace_bytes, void* hip_stream)
+{
+    return compress_impl(q, k, v, modality_mask, nullptr, H, L, d, dt, budget, recent_window, merge_mode, k_out, v_out,
+                         kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
+}
+
+int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                       const float* row_lse, int H, int L, int d, lookm_dtype dt, int budget, int recent_window,
+                       lookm_merge_mode merge_mode, void* k_out, void* v_out, int32_t* kept_idx, float* scores_out,
+                       int32_t* status_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!row_lse) return LOOKM_ERR_INVALID_ARG;
+    return compress_impl(q, k, v, modality_mask, row_lse, H, L, d, dt, budget, recent_window, merge_mode, k_out, v_out,
+                         kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,

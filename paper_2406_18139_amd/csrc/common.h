@@ -74,8 +74,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 // host-side launch plumbing shared by the stage launchers (api.hip owns validation)
 namespace lookm_host {
 
-int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, float* scores,
-                  float* scratch, hipStream_t st);
+// lse_in: optional caller-supplied natural-log row log-sum-exp [H, L]; when given, pass 1 is skipped
+int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, const float* lse_in,
+                  float* scores, float* scratch, hipStream_t st);
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st);

@@ -107,7 +107,7 @@ __global__ void __launch_bounds__(256) k_score_lse_generic(const T* __restrict__
 template <typename T>
 __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restrict__ q, const T* __restrict__ k, int L,
                                                               int d, float scale2, const float* __restrict__ lse2,
-                                                              float* __restrict__ scores)
+                                                              float lse_scale, float* __restrict__ scores)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* qt = smem;
@@ -131,7 +131,7 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
         for (int r = 0; r < 4; ++r) {
             const int row = ib * TS + ty * 4 + r;
             if (row >= L) continue;
-            const float lr = lse2[row];
+            const float lr = lse2[row] * lse_scale;   // base-2 log-sum-exp of the row
             for (int c = 0; c < 4; ++c) {
                 const int col = jb * TS + tx * 4 + c;
                 if (col <= row) colsum[c] += exp2f(fmaf(acc[r][c], scale2, -lr));
@@ -156,12 +156,13 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
 
 namespace lookm_host {
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, float* scratch,
-                       hipStream_t st);
+int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, const float* lse_in,
+                       float* scores, float* scratch, hipStream_t st);
 size_t scores_mfma_scratch_floats(int H, int L);
 
 template <typename T>
-static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, float* lse, float* scores, hipStream_t st)
+static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, float* lse, const float* lse_in,
+                                 float* scores, hipStream_t st)
 {
     const int nb = (L + lookm::TS - 1) / lookm::TS;
     size_t lds = (size_t)2 * d * lookm::TS * sizeof(float);
@@ -177,9 +178,13 @@ static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, fl
         if (e1 != hipSuccess || e2 != hipSuccess) return LOOKM_ERR_DEVICE;
         attr_done = true;
     }
-    hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, L, d, scale2, lse);
-    mark(LOOKM_K_SCORE_LSE);
-    hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, grid, block, lds, st, q, k, L, d, scale2, lse, scores);
+    if (!lse_in) {
+        hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, L, d, scale2, lse);
+        mark(LOOKM_K_SCORE_LSE);
+    }
+    // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
+    hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, grid, block, lds, st, q, k, L, d, scale2,
+                       lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, scores);
     mark(LOOKM_K_SCORE_COLSUM);
     return hip_ok(hipGetLastError());
 }
@@ -189,14 +194,14 @@ size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)
     return (dt == LOOKM_BF16 && d == 128) ? scores_mfma_scratch_floats(H, L) : 0;
 }
 
-int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, float* scores,
-                  float* scratch, hipStream_t st)
+int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, const float* lse_in,
+                  float* scores, float* scratch, hipStream_t st)
 {
     if (dt == LOOKM_BF16) {
-        if (d == 128) return launch_scores_mfma(q, k, H, L, d, lse, scores, scratch, st);
-        return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, L, d, lse, scores, st);
+        if (d == 128) return launch_scores_mfma(q, k, H, L, d, lse, lse_in, scores, scratch, st);
+        return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, L, d, lse, lse_in, scores, st);
     }
-    return launch_scores_generic((const float*)q, (const float*)k, H, L, d, lse, scores, st);
+    return launch_scores_generic((const float*)q, (const float*)k, H, L, d, lse, lse_in, scores, st);
 }
 
 }  // namespace lookm_host

@@ -94,7 +94,7 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT)
 template <int PASS>
 __global__ void __launch_bounds__(256, 3)
 k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2, int C, int U,
-             const float* __restrict__ lse2, float* __restrict__ part_a, float* __restrict__ part_b)
+             const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a, float* __restrict__ part_b)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
@@ -170,7 +170,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         if (PASS == 2 && tid < BX) stage_l = (x0 + tid < L) ? lse_h[x0 + tid] : INFINITY;   // negated at store time
     };
     auto store_tile = [&](int buf) {
-        if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l;   // rows past the end: -inf, they contribute 0
+        if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
@@ -325,8 +325,8 @@ size_t scores_mfma_scratch_floats(int H, int L)
     return (size_t)2 * H * G * nS * lookm::BS;
 }
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, float* scores, float* scratch,
-                       hipStream_t st)
+int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, const float* lse_in,
+                       float* scores, float* scratch, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
@@ -338,13 +338,16 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
-    hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U1,
-                       lse, part_a, part_b);
-    mark(LOOKM_K_SCORE_LSE);
-    hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
-    mark(LOOKM_K_SCORE_LSE_FOLD);
+    if (!lse_in) {
+        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, scale2, C,
+                           U1, lse, 1.0f, part_a, part_b);
+        mark(LOOKM_K_SCORE_LSE);
+        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
+        mark(LOOKM_K_SCORE_LSE_FOLD);
+    }
+    // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
     hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
-                       lse, part_a, part_b);
+                       lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b);
     mark(LOOKM_K_SCORE_COLSUM);
     hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);

@@ -30,7 +30,7 @@ F32, BF16 = 0, 1
 
 EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
-           "lookm_compress_profile"]
+           "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -66,6 +66,10 @@ def lib() -> ctypes.CDLL:
         L.lookm_compress_profile.restype = I
         L.lookm_compress_profile.argtypes = [vp, vp, vp, vp, I, I, I, I, I, I, I, vp, vp, vp, vp, vp, vp, sz, vp, I,
                                              ctypes.POINTER(ctypes.c_float)]
+        L.lookm_scores_lse.restype = I
+        L.lookm_scores_lse.argtypes = [vp, vp, vp, I, I, I, I, vp, vp, sz, vp]
+        L.lookm_compress_lse.restype = I
+        L.lookm_compress_lse.argtypes = [vp, vp, vp, vp, vp, I, I, I, I, I, I, I, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lookm_scores.restype = I
         L.lookm_scores.argtypes = [vp, vp, I, I, I, I, vp, vp, sz, vp]
         L.lookm_select.restype = I
@@ -147,9 +151,11 @@ class Compressed:
 
 def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode,
                    want_scores: bool = False, out: Optional[Compressed] = None,
-                   workspace: Optional[torch.Tensor] = None, check: bool = True) -> Compressed:
+                   workspace: Optional[torch.Tensor] = None, check: bool = True,
+                   row_lse: Optional[torch.Tensor] = None) -> Compressed:
     """One layer's compression.  q, k, v: GPU tensors [H, L, d]; modality_mask: GPU uint8 [L].
-    ``check=True`` synchronises to read the device status word and raises on failure."""
+    ``check=True`` synchronises to read the device status word and raises on failure.
+    With ``row_lse`` (GPU float32 [H, L]) the call forwards to lookm_compress_lse."""
     H, L, d = q.shape
     dt = _dt(q)
     B = int(budget)
@@ -159,11 +165,17 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
     if workspace is None:
         workspace = alloc_workspace(H, L, d, min(max(B, 0), L), dt, dev)
     wp, wn = _ws_ptr(workspace)
-    rc = lib().lookm_compress(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
-                              H, L, d, dt, B, int(recent_window), _mode(merge_mode),
-                              _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"), _dev(out.kept_idx, "kept_idx"),
-                              _dev(out.scores, "scores") if out.scores is not None else None,
-                              _dev(out.status, "status"), wp, wn, _stream())
+    tail = (H, L, d, dt, B, int(recent_window), _mode(merge_mode),
+            _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"), _dev(out.kept_idx, "kept_idx"),
+            _dev(out.scores, "scores") if out.scores is not None else None,
+            _dev(out.status, "status"), wp, wn, _stream())
+    head = (_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"))
+    if row_lse is None:
+        rc = lib().lookm_compress(*head, *tail)
+    else:
+        if row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (H, L):
+            raise ValueError("row_lse must be float32 [H, L]")
+        rc = lib().lookm_compress_lse(*head, _dev(row_lse, "row_lse"), *tail)
     if rc != OK:
         raise LookmError(rc, "lookm_compress")
     if check:
@@ -210,6 +222,22 @@ def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor
     rc = lib().lookm_scores(_dev(q, "q"), _dev(k, "k"), H, L, d, dt, scores.data_ptr(), wp, wn, _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_scores")
+    return scores
+
+
+def lookm_scores_lse(q, k, row_lse, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    H, L, d = q.shape
+    dt = _dt(q)
+    if row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (H, L):
+        raise ValueError("row_lse must be float32 [H, L]")
+    scores = torch.empty((H, L), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, 0, dt, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_scores_lse(_dev(q, "q"), _dev(k, "k"), _dev(row_lse, "row_lse"), H, L, d, dt,
+                                scores.data_ptr(), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_scores_lse")
     return scores
 
 

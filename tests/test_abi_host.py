@@ -86,6 +86,9 @@ def test_stage_calls_reject_bad_arguments():
     assert L.lookm_scores(None, FAKE, 1, 8, 8, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_scores(FAKE, FAKE, 1, 8, 12, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_UNSUPPORTED
     assert L.lookm_scores(FAKE, FAKE, 1, 8, 8, 0, FAKE, FAKE, 8, None) == lookm.ERR_WORKSPACE
+    assert L.lookm_scores_lse(FAKE, FAKE, None, 1, 8, 8, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
+    assert L.lookm_compress_lse(FAKE, FAKE, FAKE, FAKE, None, 2, 64, 64, 0, 32, 8, 1, FAKE, FAKE, FAKE, None, FAKE, FAKE,
+                                1 << 30, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_select(FAKE, FAKE, 1, 8, 9, 0, FAKE, FAKE, FAKE, None) == lookm.ERR_BUDGET_RANGE
     assert L.lookm_select(FAKE, None, 1, 8, 4, 0, FAKE, FAKE, FAKE, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_nearest(FAKE, FAKE, FAKE, 1, 8, 8, 0, 0, FAKE, FAKE, FAKE, 1 << 20, None) == lookm.ERR_BUDGET_RANGE

@@ -90,3 +90,18 @@ def test_device_status_on_budget_below_protected():
     with pytest.raises(lookm.LookmError) as e:
         lookm.lookm_compress(q.cuda(), k.cuda(), v.cuda(), mask.cuda(), 100, 16, "averaged")   # 128 protected
     assert e.value.code == lookm.ERR_BUDGET_BELOW_PROTECTED
+
+
+def test_compress_with_supplied_row_lse_matches_the_full_path():
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w, heads=[0, 5, 9, 30])
+    lse = torch.from_numpy(oracle.row_lse(q, k)).float().cuda()
+    args = [t.cuda() for t in (q, k, v, mask)]
+    a = lookm.lookm_compress(*args, w.budget(), w.M, "pivotal", want_scores=True)
+    b = lookm.lookm_compress(*args, w.budget(), w.M, "pivotal", want_scores=True, row_lse=lse)
+    ref = oracle.compress(q, k, v, mask.numpy(), w.budget(), w.M, "pivotal")
+    sb = b.scores.cpu().numpy().astype(np.float64)
+    assert (np.abs(sb - ref["scores"]) / ref["scores"]).max() < 2e-5
+    assert b.kept_idx.cpu().numpy().tolist() == ref["kept"].tolist()
+    assert torch.equal(a.kept_idx, b.kept_idx)
+    assert np.abs(b.k_out.float().cpu().numpy() - ref["k_out"]).max() <= 2e-2

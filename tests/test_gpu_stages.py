@@ -60,6 +60,21 @@ def test_scores_zero_queries_closed_form():
     np.testing.assert_allclose(s, np.cumsum(inv[::-1])[::-1], rtol=2e-6)
 
 
+@pytest.mark.parametrize("H,L,d,dtype", [(3, 700, 128, torch.bfloat16), (2, 333, 64, torch.bfloat16),
+                                         (2, 256, 64, torch.float32)])
+def test_scores_from_a_supplied_row_lse(H, L, d, dtype):
+    # the row log-sum-exp a prefill kernel would hold (here: the oracle's, rounded to fp32) replaces pass 1
+    q, k = rand_qk(H, L, d, dtype, seed=L + d)
+    lse = torch.from_numpy(oracle.row_lse(q, k)).float()
+    s = lookm.lookm_scores_lse(q.cuda(), k.cuda(), lse.cuda()).cpu().numpy().astype(np.float64)
+    ref = oracle.scores(q, k)
+    rel = np.abs(s - ref) / ref
+    print(f"scores from row_lse H={H} L={L} d={d} {dtype}: max rel err {rel.max():.3e}")
+    assert rel.max() < 2e-5
+    own = lookm.lookm_scores(q.cuda(), k.cuda()).cpu().numpy().astype(np.float64)
+    assert (np.abs(own - s) / ref).max() < 1e-5       # both routes agree
+
+
 def select_case(scores, mask, B, M):
     sg = torch.from_numpy(np.asarray(scores, np.float32)).cuda()
     mg = torch.from_numpy(np.asarray(mask, np.uint8)).cuda()

@@ -22,6 +22,8 @@ MUTANTS = [
     ("qk_swapped", "dot += (double)q[(size_t)i * d + c] * (double)k[(size_t)j * d + c];",
      "dot += (double)q[(size_t)j * d + c] * (double)k[(size_t)i * d + c];"),
     ("unnormalised_rows", "scores[j] += s[j] / z;", "scores[j] += s[j];"),
+    ("lse_without_max_shift", "lse[i] = top + log(z);", "lse[i] = log(z);"),
+    ("lse_without_scale", "t[j] = acc * inv_root_d;", "t[j] = acc;"),
     ("tie_to_higher_position", "return (x->pos > y->pos) - (x->pos < y->pos); /* tie", "return (x->pos < y->pos) - (x->pos > y->pos); /* tie"),
     ("lowest_scores_kept", "if (x->key > y->key) return -1;   /* higher score first */\n    if (x->key < y->key) return 1;",
      "if (x->key > y->key) return 1;\n    if (x->key < y->key) return -1;"),

@@ -147,3 +147,25 @@ def test_bf16_inputs_are_widened_exactly():
     k = torch.randn(L, d, generator=g).to(torch.bfloat16)
     np.testing.assert_allclose(oracle.scores(q, k), dense_scores_numpy(q.double().numpy(), k.double().numpy()),
                                rtol=1e-12)
+
+
+def test_row_lse_matches_library_logsumexp_and_rebuilds_the_scores():
+    L, d = 70, 32
+    g = torch.Generator().manual_seed(77)
+    q = torch.randn(L, d, generator=g) * 1.5
+    k = torch.randn(L, d, generator=g)
+    logits = (q.double() @ k.double().T) / math.sqrt(d)
+    causal = torch.full((L, L), float("-inf"), dtype=torch.float64).triu(1)
+    ref = torch.logsumexp(logits + causal, dim=-1).numpy()
+    lse = oracle.row_lse(q, k)
+    np.testing.assert_allclose(lse, ref, rtol=1e-13, atol=1e-13)
+    assert abs(lse[0] - float(logits[0, 0])) < 1e-14        # row 0 has a single term
+    # A_p[i, j] = exp(s_ij - lse_i): its column sums are the accumulated scores
+    A_p = torch.exp(logits + causal - torch.from_numpy(lse)[:, None]).numpy()
+    np.testing.assert_allclose(A_p.sum(0), oracle.scores(q, k), rtol=1e-12)
+
+
+def test_row_lse_closed_form_for_zero_queries():
+    L, d = 50, 8
+    k = np.random.default_rng(3).standard_normal((L, d)).astype(np.float32)
+    np.testing.assert_allclose(oracle.row_lse(np.zeros((L, d), np.float32), k), np.log(np.arange(1, L + 1)), rtol=1e-14)
