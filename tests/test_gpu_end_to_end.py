@@ -61,6 +61,15 @@ def test_stack_prompts_two_layers_each():
         for layer in (0, 31):
             st = parity.run_and_check(w, "weighted", heads=[0, 1, 2, 3], layer=layer, oracle_heads=[1])
             print(w.name, layer, st)
+            assert st["kept_diff_heads"] == 0
+
+
+def test_stack_long_prompts_one_layer_each():
+    # the 9K and 12K prompts of the stack: GPU on four heads, oracle on two of them
+    for w, layer in zip(W.stack_prompts()[2:], (15, 7)):
+        st = parity.run_and_check(w, "weighted", heads=[4, 11, 18, 25], layer=layer, oracle_heads=[0, 3])
+        print(w.name, layer, st)
+        assert st["kept_diff_heads"] == 0
 
 
 def test_text_prior_off():
@@ -105,3 +114,21 @@ def test_compress_with_supplied_row_lse_matches_the_full_path():
     assert b.kept_idx.cpu().numpy().tolist() == ref["kept"].tolist()
     assert torch.equal(a.kept_idx, b.kept_idx)
     assert np.abs(b.k_out.float().cpu().numpy() - ref["k_out"]).max() <= 2e-2
+
+
+@pytest.mark.parametrize("H,L,n_img,img_tokens,spans,rho,M", [
+    (1, 1, 0, 0, (1,), 0.5, 0),                    # a single text token
+    (3, 63, 1, 40, (10, 13), 0.25, 5),             # shorter than one tile; 3 heads share the XCDs unevenly
+    (9, 257, 2, 100, (20, 17, 20), 0.1, 16),       # one row past a strip; 9 heads = two rounds over the XCDs
+    (5, 1000, 3, 300, (30, 25, 25, 20), 0.02, 0),  # almost everything evicted, no recent window
+    (2, 700, 2, 320, (20, 20, 20), 0.97, 64),      # almost nothing evicted
+    (4, 513, 1, 500, (6, 7), 0.0, 3),              # no image token conserved (k_img = 0)
+])
+def test_odd_shapes_on_the_matrix_core_path(H, L, n_img, img_tokens, spans, rho, M):
+    w = W.Workload(f"odd_{H}_{L}", 9, H, 128, "bf16", spans, img_tokens, 8, 0.3, rho, M, ("weighted",))
+    assert w.L == L and w.n_img == n_img
+    for mode in ("weighted", "pivotal"):
+        st = parity.run_and_check(w, mode)
+        print(w.name, mode, st)
+        assert st["kept_diff_heads"] == 0
+        assert st["nearest_tie_rows"] <= max(1, 2e-3 * st["rows_matched"])
