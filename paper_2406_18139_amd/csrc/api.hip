@@ -11,7 +11,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t lse, scores, evicted, assign, sim, rnorm, offsets, member_pos, member_w, partials, total;
+    size_t lse, scores, evicted, assign, sim, rnorm, plan, member_pos, member_w, partials, total;
 };
 
 Layout make_layout(int H, int L, int d, int dt, int budget)
@@ -25,7 +25,7 @@ Layout make_layout(int H, int L, int d, int dt, int budget)
     w.assign = o;  o += align_up(HE * sizeof(int32_t));
     w.sim = o;     o += align_up(HE * sizeof(float));
     w.rnorm = o;   o += align_up(HL * sizeof(float));
-    w.offsets = o; o += align_up((size_t)H * (budget + 1) * sizeof(int32_t));
+    w.plan = o;    o += align_up((size_t)H * budget * 4 * sizeof(int32_t));   // merge plan, one int4 per slot
     w.member_pos = o; o += align_up(HE * sizeof(int32_t));
     w.member_w = o;   o += align_up(HE * sizeof(float));
     // the score partials and the matching partials are never live at the same time: one slice serves both
@@ -136,7 +136,7 @@ int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L
     // an empty list (budget 0, or budget L) may be passed as NULL
     if ((budget > 0 && !kept_idx) || (budget < L && !evicted_idx)) return LOOKM_ERR_INVALID_ARG;
     return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted_idx,
-                                     status_out, (hipStream_t)hip_stream);
+                                     status_out, nullptr, 0, LOOKM_F32, nullptr, (hipStream_t)hip_stream);
 }
 
 int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted_idx, int H, int L, int d,
@@ -153,7 +153,7 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
-                                      assign, sim, at<void>(workspace, w.partials), (hipStream_t)hip_stream);
+                                      false, assign, sim, at<void>(workspace, w.partials), (hipStream_t)hip_stream);
 }
 
 int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int32_t* evicted_idx,
@@ -173,7 +173,7 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, budget);
     return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
-                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.member_pos),
+                                    at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
 }
 
@@ -205,16 +205,20 @@ static int compress_impl(const void* q, const void* k, const void* v, const uint
     rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores,
                                    at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
-    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
+    // the matching needs the inverse key norms; they ride along with the selection's launch
+    const bool match = merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
+    float* rnorm = at<float>(workspace, w.rnorm);
+    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out,
+                                   match ? k : nullptr, d, dt, match ? rnorm : nullptr, st);
     if (rc != LOOKM_OK) return rc;
     if (merge_mode != LOOKM_MERGE_NONE && budget < L) {
         if (budget == 0) return LOOKM_OK;   // nothing conserved: nothing to merge into
-        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
-                                        assign, sim, at<void>(workspace, w.partials), st);
+        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, rnorm, true, assign, sim,
+                                        at<void>(workspace, w.partials), st);
         if (rc != LOOKM_OK) return rc;
     }
     return lookm_host::launch_merge(k, v, kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)merge_mode,
-                                    at<int32_t>(workspace, w.offsets), at<int32_t>(workspace, w.member_pos),
+                                    at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), k_out, v_out, st);
 }
 

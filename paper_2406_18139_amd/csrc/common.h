@@ -78,13 +78,18 @@ namespace lookm_host {
 int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, const float* lse_in,
                   float* scores, float* scratch, hipStream_t st);
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
+// k_rows / rnorm: optional; when given, extra workgroups of the same launch write rnorm[H*L] = 1/||k row||
+// (work that does not depend on the selection and would otherwise wait behind its one workgroup per head)
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
-                  int32_t* evicted, int32_t* status, hipStream_t st);
+                  int32_t* evicted, int32_t* status, const void* k_rows, int d, lookm_dtype dt, float* rnorm,
+                  hipStream_t st);
+// rnorm_ready: rnorm already holds the inverse row norms (written by launch_select)
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,
-                   int budget, float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st);
+                   int budget, float* rnorm, bool rnorm_ready, int32_t* assign, float* sim, void* scratch,
+                   hipStream_t st);
 size_t nearest_scratch_bytes(int H, int L, int d, lookm_dtype dt, int budget);
 int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_t* evicted, const int32_t* assign,
-                 const float* sim, int H, int L, int d, lookm_dtype dt, int budget, int mode, int32_t* offsets,
+                 const float* sim, int H, int L, int d, lookm_dtype dt, int budget, int mode, int32_t* plan_words,
                  int32_t* member_pos, float* member_w, void* k_out, void* v_out, hipStream_t st);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }

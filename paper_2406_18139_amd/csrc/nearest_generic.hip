@@ -126,12 +126,14 @@ size_t nearest_mfma_scratch_bytes(int H, int L, int B);
 
 template <typename T>
 static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, int budget,
-                            float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st, bool mfma)
+                            float* rnorm, bool rnorm_ready, int32_t* assign, float* sim, void* scratch, hipStream_t st,
+                            bool mfma)
 {
     const int Le = L - budget;
     if (Le == 0) return LOOKM_OK;
     const size_t rows = (size_t)H * L;
-    hipLaunchKernelGGL(lookm::k_rnorm<T>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, k, rows, d, rnorm);
+    if (!rnorm_ready)
+        hipLaunchKernelGGL(lookm::k_rnorm<T>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, k, rows, d, rnorm);
     mark(LOOKM_K_RNORM);
     if (mfma) return launch_nearest_mfma(k, kept, evicted, H, L, budget, rnorm, assign, sim, scratch, st);
     size_t lds = (size_t)2 * d * lookm::NT_TS * sizeof(float);
@@ -156,12 +158,14 @@ size_t nearest_scratch_bytes(int H, int L, int d, lookm_dtype dt, int budget)
 }
 
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,
-                   int budget, float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st)
+                   int budget, float* rnorm, bool rnorm_ready, int32_t* assign, float* sim, void* scratch,
+                   hipStream_t st)
 {
     if (dt == LOOKM_BF16)
-        return launch_nearest_t((const lookm::bf16_t*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, scratch,
-                                st, d == 128);
-    return launch_nearest_t((const float*)k, kept, evicted, H, L, d, budget, rnorm, assign, sim, scratch, st, false);
+        return launch_nearest_t((const lookm::bf16_t*)k, kept, evicted, H, L, d, budget, rnorm, rnorm_ready, assign,
+                                sim, scratch, st, d == 128);
+    return launch_nearest_t((const float*)k, kept, evicted, H, L, d, budget, rnorm, rnorm_ready, assign, sim, scratch,
+                            st, false);
 }
 
 }  // namespace lookm_host

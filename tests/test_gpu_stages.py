@@ -100,6 +100,24 @@ def test_select_matches_oracle_with_ties(seed):
             assert ev[h].tolist() == re_.tolist(), (L, M, B, h)
 
 
+def test_select_scores_in_a_narrow_range_or_all_equal():
+    # keys are re-based to the head's own range before the radix digits are taken
+    rng = np.random.default_rng(5)
+    L, M = 3000, 10
+    mask = (rng.random(L) < 0.9).astype(np.uint8)
+    P = oracle.protected_count(mask, M)
+    narrow = (1.0 + rng.integers(0, 50, (1, L)) * 2.0 ** -23).astype(np.float32)     # 50 adjacent floats
+    # positive, as Eq. 4 scores are, and within what the oracle's literal binary64 add of Eq. 5 resolves
+    wide = (10.0 ** rng.uniform(-7, 7, (1, L))).astype(np.float32)
+    same = np.full((1, L), 0.37, np.float32)
+    two = np.where(rng.random((1, L)) < 0.5, np.float32(1.0e-7), np.float32(3.0e7)).astype(np.float32)
+    for scores in (narrow, wide, same, two):
+        for B in (P + 1, P + 700, L - 1):
+            kept, ev = select_case(scores, mask, B, M)
+            rk, re_ = oracle.select(scores[0].astype(np.float64), mask, B, M)
+            assert kept[0].tolist() == rk.tolist() and ev[0].tolist() == re_.tolist(), B
+
+
 def test_select_degenerate_cases():
     L = 300
     scores = np.random.default_rng(0).random((2, L)).astype(np.float32)
@@ -184,6 +202,9 @@ def test_nearest_exact_ties_and_zero_keys():
     (2, 256, 154, 64, torch.float32),
     (1, 120, 40, 8, torch.float32),
     (1, 300, 77, 256, torch.bfloat16),
+    (2, 9000, 2100, 16, torch.bfloat16),     # register-resident sort, 8 entries per thread
+    (1, 7000, 5200, 8, torch.float32),       # budget too large for 16 counter rows in LDS: general sort
+    (1, 20000, 1500, 8, torch.bfloat16),     # more than 16 K evicted tokens: general sort
 ])
 def test_merge_matches_oracle(mode, H, L, B, d, dtype):
     g = torch.Generator().manual_seed(L * 3 + B)
