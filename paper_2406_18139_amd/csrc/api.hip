@@ -108,7 +108,7 @@ static int scores_impl(const void* q, const void* k, const float* row_lse, int H
     rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, 0);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, 0);
-    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores_out,
+    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores_out, nullptr,
                                      at<float>(workspace, w.partials), (hipStream_t)hip_stream);
 }
 
@@ -136,7 +136,7 @@ int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L
     // an empty list (budget 0, or budget L) may be passed as NULL
     if ((budget > 0 && !kept_idx) || (budget < L && !evicted_idx)) return LOOKM_ERR_INVALID_ARG;
     return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted_idx,
-                                     status_out, nullptr, 0, LOOKM_F32, nullptr, (hipStream_t)hip_stream);
+                                     status_out, (hipStream_t)hip_stream);
 }
 
 int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted_idx, int H, int L, int d,
@@ -202,18 +202,18 @@ static int compress_impl(const void* q, const void* k, const void* v, const uint
     int32_t* assign = at<int32_t>(workspace, w.assign);
     float* sim = at<float>(workspace, w.sim);
 
-    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores,
-                                   at<float>(workspace, w.partials), st);
-    if (rc != LOOKM_OK) return rc;
-    // the matching needs the inverse key norms; they ride along with the selection's launch
+    // the matching needs the inverse key norms; the matrix-core score pass writes them from the key rows it holds
     const bool match = merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
     float* rnorm = at<float>(workspace, w.rnorm);
-    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out,
-                                   match ? k : nullptr, d, dt, match ? rnorm : nullptr, st);
+    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores,
+                                   match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
+    if (rc != LOOKM_OK) return rc;
+    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
     if (rc != LOOKM_OK) return rc;
     if (merge_mode != LOOKM_MERGE_NONE && budget < L) {
         if (budget == 0) return LOOKM_OK;   // nothing conserved: nothing to merge into
-        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, rnorm, true, assign, sim,
+        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, rnorm,
+                                        lookm_host::scores_write_rnorm(d, dt), assign, sim,
                                         at<void>(workspace, w.partials), st);
         if (rc != LOOKM_OK) return rc;
     }

@@ -75,15 +75,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 namespace lookm_host {
 
 // lse_in: optional caller-supplied natural-log row log-sum-exp [H, L]; when given, pass 1 is skipped
+// rnorm: optional [H, L]; the matrix-core path (see scores_write_rnorm) fills it with 1/||k row|| on the way
 int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, const float* lse_in,
-                  float* scores, float* scratch, hipStream_t st);
+                  float* scores, float* rnorm, float* scratch, hipStream_t st);
+inline bool scores_write_rnorm(int d, lookm_dtype dt) { return dt == LOOKM_BF16 && d == 128; }
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
-// k_rows / rnorm: optional; when given, extra workgroups of the same launch write rnorm[H*L] = 1/||k row||
-// (work that does not depend on the selection and would otherwise wait behind its one workgroup per head)
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
-                  int32_t* evicted, int32_t* status, const void* k_rows, int d, lookm_dtype dt, float* rnorm,
-                  hipStream_t st);
-// rnorm_ready: rnorm already holds the inverse row norms (written by launch_select)
+                  int32_t* evicted, int32_t* status, hipStream_t st);
+// rnorm_ready: rnorm already holds the inverse key norms (written by launch_scores)
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,
                    int budget, float* rnorm, bool rnorm_ready, int32_t* assign, float* sim, void* scratch,
                    hipStream_t st);

@@ -85,6 +85,18 @@ k_bucket(const int32_t* __restrict__ assign, const int32_t* __restrict__ evicted
         }
         n_own += __popcll(mb);
     }
+    // the wave's first two rows of own entries: their slot, position and cosine are fetched now and arrive while
+    // the offsets and the plan are being worked out
+    int pre_key[2], pre_pos[2];
+    float pre_w[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const bool valid = u * 64 + lane < n_own;
+        const int e = min(seg + (valid ? (int)own[u * 64 + lane] : 0), Le - 1);
+        pre_key[u] = assign[e];
+        pre_pos[u] = evicted[e];
+        pre_w[u] = sim[e];
+    }
     if (lane == 0) wbelow[wave] = below_wave;
     __syncthreads();
 
@@ -151,23 +163,27 @@ k_bucket(const int32_t* __restrict__ assign, const int32_t* __restrict__ evicted
     }
     __syncthreads();
 
-    for (int c0 = 0; c0 < n_own; c0 += 64) {
-        const bool valid = c0 + lane < n_own;
-        const int e = min(seg + (valid ? (int)own[c0 + lane] : 0), Le - 1);
-        const int key = valid ? min(max(assign[e], 0), B - 1) - lo : 0;
-        const int pos = evicted[e];          // the set lists positions (ascending) and their cosines
-        const float sw = sim[e];
+    // one 64-entry row of the wave's list: rank lanes with equal slots, store, advance the slots' offsets
+    auto place = [&](bool valid, int raw_slot, int pos, float sw) {
+        const int key = valid ? min(max(raw_slot, 0), B - 1) - lo : 0;
         const uint64_t peers = match_key(key, valid, nbits);
         int base = 0;
         if (valid) {
             base = cnt[wave * ns + key];
             const int dst = base + mask_rank(peers);
-            member_pos[dst] = pos;
+            member_pos[dst] = pos;           // the set lists positions (ascending) and their cosines
             member_w[dst] = sw;
         }
         __builtin_amdgcn_wave_barrier();
         if (valid && (peers >> lane) == 1ull) cnt[wave * ns + key] = base + __popcll(peers);   // highest peer updates
         __builtin_amdgcn_wave_barrier();
+    };
+    if (n_own > 0) place(lane < n_own, pre_key[0], pre_pos[0], pre_w[0]);
+    if (n_own > 64) place(64 + lane < n_own, pre_key[1], pre_pos[1], pre_w[1]);
+    for (int c0 = 128; c0 < n_own; c0 += 64) {
+        const bool valid = c0 + lane < n_own;
+        const int e = min(seg + (valid ? (int)own[c0 + lane] : 0), Le - 1);
+        place(valid, assign[e], evicted[e], sim[e]);
     }
 }
 

@@ -157,7 +157,7 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
 namespace lookm_host {
 
 int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, const float* lse_in,
-                       float* scores, float* scratch, hipStream_t st);
+                       float* scores, float* rnorm, float* scratch, hipStream_t st);
 size_t scores_mfma_scratch_floats(int H, int L);
 
 template <typename T>
@@ -195,10 +195,10 @@ size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)
 }
 
 int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* lse, const float* lse_in,
-                  float* scores, float* scratch, hipStream_t st)
+                  float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     if (dt == LOOKM_BF16) {
-        if (d == 128) return launch_scores_mfma(q, k, H, L, d, lse, lse_in, scores, scratch, st);
+        if (scores_write_rnorm(d, dt)) return launch_scores_mfma(q, k, H, L, d, lse, lse_in, scores, rnorm, scratch, st);
         return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, L, d, lse, lse_in, scores, st);
     }
     return launch_scores_generic((const float*)q, (const float*)k, H, L, d, lse, lse_in, scores, st);

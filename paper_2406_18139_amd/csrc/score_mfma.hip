@@ -90,11 +90,14 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT)
 // followed by independent VALU work in the same wave runs back to back), so the kernel keeps each
 // wave's code simple - MFMA chains, then the epilogue - and is sized for three resident waves per SIMD.
 //   PASS 1 writes part_a = running max, part_b = running sum (base-2 domain) per (chunk, stationary row).
-//   PASS 2 writes part_a = partial column sum per (chunk, stationary row).
+//   PASS 2 writes part_a = partial column sum per (chunk, stationary row).  Its stationary rows are keys: when
+//   `rnorm` is given, the workgroup of a strip's first chunk also writes rnorm[h, j] = 1 / ||k_j|| (0 for a
+//   zero key) for the matching of Eq. 9, from the registers it holds anyway - the keys are not read again for it.
 template <int PASS>
 __global__ void __launch_bounds__(256, 3)
 k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2, int C, int U,
-             const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a, float* __restrict__ part_b)
+             const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a, float* __restrict__ part_b,
+             float* __restrict__ rnorm)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
@@ -179,6 +182,38 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     load_tile(x_begin, 0);
     store_tile(0);
+    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT)) {
+        // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
+        // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
+        // partial sums, number p over groups p and p + 8, then a pairwise tree), so both give the same bits
+        // and the stage call lookm_nearest reproduces the matching of the whole path exactly.
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            float part[4];   // partial sums number 2*j + half
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float ss = 0.f;
+#pragma unroll
+                for (int rep = 0; rep < 2; ++rep) {
+                    const uint4 v = __builtin_bit_cast(uint4, sf[cb][j + 4 * rep]);
+                    const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float lo = __uint_as_float(w4[i] << 16), hi = __uint_as_float(w4[i] & 0xffff0000u);
+                        ss = fmaf(lo, lo, ss);
+                        ss = fmaf(hi, hi, ss);
+                    }
+                }
+                part[j] = ss;
+            }
+            float pair[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) pair[j] = part[j] + __shfl_xor(part[j], 32);
+            const float ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
+            const int row = w0 + cb * 32 + n;
+            if (half == 0 && row < L) rnorm[(size_t)h * L + row] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
+        }
+    }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
@@ -326,7 +361,7 @@ size_t scores_mfma_scratch_floats(int H, int L)
 }
 
 int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, const float* lse_in,
-                       float* scores, float* scratch, hipStream_t st)
+                       float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
@@ -340,14 +375,14 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
     if (!lse_in) {
         hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, scale2, C,
-                           U1, lse, 1.0f, part_a, part_b);
+                           U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
         mark(LOOKM_K_SCORE_LSE);
         hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
         mark(LOOKM_K_SCORE_LSE_FOLD);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
     hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
-                       lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b);
+                       lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
     mark(LOOKM_K_SCORE_COLSUM);
     hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);
