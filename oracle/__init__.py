@@ -65,12 +65,18 @@ def lib() -> ctypes.CDLL:
         L.oracle_protected_count.restype = I
         L.oracle_select_head.argtypes = [dp, up, I, I, I, ip, ip]
         L.oracle_select_head.restype = I
+        L.oracle_select_rule_head.argtypes = [dp, up, I, I, I, I, ip, ip]
+        L.oracle_select_rule_head.restype = I
+        L.oracle_budget_from_ratios.argtypes = [I, ctypes.c_double, ctypes.c_double, ip, ip]
+        L.oracle_budget_from_ratios.restype = I
         L.oracle_nearest_head.argtypes = [fp, I, ip, I, ip, I, ip, dp]
         L.oracle_nearest_head.restype = None
         L.oracle_merge_head.argtypes = [fp, I, ip, I, ip, I, ip, dp, I, dp]
         L.oracle_merge_head.restype = I
         L.oracle_compress.argtypes = [fp, fp, fp, up, I, I, I, I, I, I, dp, ip, ip, ip, dp, dp, dp]
         L.oracle_compress.restype = I
+        L.oracle_compress_rule.argtypes = [fp, fp, fp, up, I, I, I, I, I, I, I, dp, ip, ip, ip, dp, dp, dp]
+        L.oracle_compress_rule.restype = I
         L.oracle_num_threads.argtypes = []
         L.oracle_num_threads.restype = I
         _lib = L
@@ -134,16 +140,32 @@ def protected_count(mask, recent_window: int) -> int:
     return int(lib().oracle_protected_count(_p(m, ctypes.c_uint8), m.shape[0], int(recent_window)))
 
 
-def select(scores_1d, mask, budget: int, recent_window: int):
-    """Eq. 5-8 for one head: -> (kept [B] int32 ascending, evicted [L-B] int32 ascending)."""
+RULES = {"protect_text": 0, "literal": 1}
+
+
+def budget_from_ratios(L: int, alpha_recent: float, alpha_important: float):
+    """Section 4 "Implementation Details": M = alpha_1 L, N = alpha_2 L -> (recent_window M, budget S = N + M)."""
+    M = np.zeros(1, np.int32)
+    N = np.zeros(1, np.int32)
+    rc = lib().oracle_budget_from_ratios(int(L), float(alpha_recent), float(alpha_important),
+                                         _p(M, ctypes.c_int32), _p(N, ctypes.c_int32))
+    if rc < 0:
+        raise OracleError(rc)
+    return int(M[0]), int(rc)
+
+
+def select(scores_1d, mask, budget: int, recent_window: int, rule="protect_text"):
+    """Eq. 5-8 for one head: -> (kept [B] int32 ascending, evicted [L-B] int32 ascending).
+    rule "protect_text": all text tokens must fit in the budget; "literal": Eq. 8 as printed, for any budget."""
     s = np.ascontiguousarray(scores_1d, dtype=np.float64)
     m = _mask(mask)
     L = s.shape[0]
     B = int(budget)
     kept = np.empty(max(B, 0), dtype=np.int32)
     ev = np.empty(max(L - B, 0), dtype=np.int32)
-    rc = lib().oracle_select_head(_p(s, ctypes.c_double), _p(m, ctypes.c_uint8), L, B, int(recent_window),
-                                  _p(kept, ctypes.c_int32), _p(ev, ctypes.c_int32))
+    rule = RULES[rule] if isinstance(rule, str) else int(rule)
+    rc = lib().oracle_select_rule_head(_p(s, ctypes.c_double), _p(m, ctypes.c_uint8), L, B, int(recent_window), rule,
+                                       _p(kept, ctypes.c_int32), _p(ev, ctypes.c_int32))
     if rc != OK:
         raise OracleError(rc)
     return kept, ev
@@ -178,7 +200,7 @@ def merge(x_2d, kept, evicted, assign, sim, mode) -> np.ndarray:
     return out
 
 
-def compress(q, k, v, mask, budget: int, recent_window: int, mode) -> dict:
+def compress(q, k, v, mask, budget: int, recent_window: int, mode, rule="protect_text") -> dict:
     """The whole path over all heads.  q, k, v: [H, L, d].  Returns a dict of NumPy arrays:
     scores [H, L] f64, kept [H, B] i32, evicted [H, Le] i32, assign [H, Le] i32, sim [H, Le] f64,
     k_out / v_out [H, B, d] f64 (unrounded)."""
@@ -196,7 +218,8 @@ def compress(q, k, v, mask, budget: int, recent_window: int, mode) -> dict:
         sim=np.empty((H, Le), np.float64), k_out=np.empty((H, Bn, d), np.float64),
         v_out=np.empty((H, Bn, d), np.float64))
     f, dd, i32 = ctypes.c_float, ctypes.c_double, ctypes.c_int32
-    rc = lib().oracle_compress(_p(q, f), _p(k, f), _p(v, f), _p(m, ctypes.c_uint8), H, L, d, B, M, mode,
+    rule = RULES[rule] if isinstance(rule, str) else int(rule)
+    rc = lib().oracle_compress_rule(_p(q, f), _p(k, f), _p(v, f), _p(m, ctypes.c_uint8), H, L, d, B, M, mode, rule,
                                _p(out["scores"], dd), _p(out["kept"], i32), _p(out["evicted"], i32),
                                _p(out["assign"], i32), _p(out["sim"], dd), _p(out["k_out"], dd), _p(out["v_out"], dd))
     if rc != OK:

@@ -127,13 +127,17 @@ int oracle_protected_count(const uint8_t *mask, int L, int M)
 }
 
 /* scores: [L] raw A_s; mask: [L], 1 = image token, 0 = text token.
- * kept: [B] ascending positions; evicted: [L - B] ascending positions.               */
-int oracle_select_head(const double *scores, const uint8_t *mask, int L, int B, int M,
-                       int32_t *kept, int32_t *evicted)
+ * kept: [B] ascending positions; evicted: [L - B] ascending positions.
+ * rule 0: every text token must be conserved - a budget below |T u R| is refused (the reading under which
+ *         "I is the union of T and the Top-N tokens" and Eq. 8 say the same thing);
+ * rule 1: Eq. 5 and Eq. 8 exactly as printed, for any M <= B <= L: when the N = B - M places do not hold all
+ *         text tokens, the boosted text tokens compete among themselves by score and no image token is conserved. */
+int oracle_select_rule_head(const double *scores, const uint8_t *mask, int L, int B, int M, int rule,
+                            int32_t *kept, int32_t *evicted)
 {
-    if (L <= 0 || M < 0) return ORACLE_ERR_ARG;
+    if (L <= 0 || M < 0 || rule < 0 || rule > 1) return ORACLE_ERR_ARG;
     if (M > L || B > L || B < M) return ORACLE_ERR_BUDGET_RANGE;
-    if (B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;
+    if (rule == 0 && B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;
 
     /* Eq. 5: A_s[T] += T_p, T_p = Max(A_s) */
     double t_p = -INFINITY;
@@ -157,6 +161,27 @@ int oracle_select_head(const double *scores, const uint8_t *mask, int L, int B, 
     qsort(evicted, (size_t)(L - B), sizeof(int32_t), int_cmp);
     free(c);
     return ORACLE_OK;
+}
+
+int oracle_select_head(const double *scores, const uint8_t *mask, int L, int B, int M,
+                       int32_t *kept, int32_t *evicted)
+{
+    return oracle_select_rule_head(scores, mask, L, B, M, 0, kept, evicted);
+}
+
+/* Section 4 "Implementation Details": recent window M = alpha_1 * L, important tokens N = alpha_2 * L
+ * (rounded to nearest), cache size S = N + M (Eq. 8 and the sentence after it).  Returns S, or a negative
+ * code when the ratios are outside [0, 1] or their sum exceeds the prompt. */
+int oracle_budget_from_ratios(int L, double alpha_recent, double alpha_important, int *M_out, int *N_out)
+{
+    if (L <= 0 || !(alpha_recent >= 0.0 && alpha_recent <= 1.0) || !(alpha_important >= 0.0 && alpha_important <= 1.0))
+        return ORACLE_ERR_ARG;
+    const int M = (int)floor(alpha_recent * (double)L + 0.5);
+    const int N = (int)floor(alpha_important * (double)L + 0.5);
+    if (M + N > L) return ORACLE_ERR_BUDGET_RANGE;
+    *M_out = M;
+    *N_out = N;
+    return M + N;
 }
 
 /* ---- Eq. 9: cosine nearest kept key for every evicted key ------------------------------ */
@@ -230,14 +255,14 @@ int oracle_merge_head(const float *x, int d, const int32_t *kept, int B,
 /* q, k, v: [H, L, d] float32; mask: [L]; outputs: scores [H, L], kept [H, B], evicted [H, L-B],
  * assign [H, L-B], sim [H, L-B], k_out / v_out [H, B, d] double.  Heads run in parallel
  * (OpenMP) when compiled with -fopenmp; each head's arithmetic is unchanged by that.      */
-int oracle_compress(const float *q, const float *k, const float *v, const uint8_t *mask,
-                    int H, int L, int d, int B, int M, int mode,
-                    double *scores, int32_t *kept, int32_t *evicted, int32_t *assign,
-                    double *sim, double *k_out, double *v_out)
+int oracle_compress_rule(const float *q, const float *k, const float *v, const uint8_t *mask,
+                         int H, int L, int d, int B, int M, int mode, int rule,
+                         double *scores, int32_t *kept, int32_t *evicted, int32_t *assign,
+                         double *sim, double *k_out, double *v_out)
 {
-    if (H <= 0 || L <= 0 || d <= 0 || M < 0 || mode < 0 || mode > 3) return ORACLE_ERR_ARG;
+    if (H <= 0 || L <= 0 || d <= 0 || M < 0 || mode < 0 || mode > 3 || rule < 0 || rule > 1) return ORACLE_ERR_ARG;
     if (M > L || B > L || B < M) return ORACLE_ERR_BUDGET_RANGE;
-    if (B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;
+    if (B < oracle_protected_count(mask, L, M) && rule == 0) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;
     const int Le = L - B;
     int rc = ORACLE_OK;
 #pragma omp parallel for schedule(dynamic, 1)
@@ -247,7 +272,7 @@ int oracle_compress(const float *q, const float *k, const float *v, const uint8_
         int32_t *kp = kept + (size_t)h * B, *ev = evicted + (size_t)h * Le, *as = assign + (size_t)h * Le;
         double *sm = sim + (size_t)h * Le;
         oracle_scores_head(qh, kh, L, d, sc);
-        int r = oracle_select_head(sc, mask, L, B, M, kp, ev);
+        int r = oracle_select_rule_head(sc, mask, L, B, M, rule, kp, ev);
         if (r == ORACLE_OK) {
             oracle_nearest_head(kh, d, kp, B, ev, Le, as, sm);
             r = oracle_merge_head(kh, d, kp, B, ev, Le, as, sm, mode, k_out + (size_t)h * B * d);
@@ -260,6 +285,14 @@ int oracle_compress(const float *q, const float *k, const float *v, const uint8_
         }
     }
     return rc;
+}
+
+int oracle_compress(const float *q, const float *k, const float *v, const uint8_t *mask,
+                    int H, int L, int d, int B, int M, int mode,
+                    double *scores, int32_t *kept, int32_t *evicted, int32_t *assign,
+                    double *sim, double *k_out, double *v_out)
+{
+    return oracle_compress_rule(q, k, v, mask, H, L, d, B, M, mode, 0, scores, kept, evicted, assign, sim, k_out, v_out);
 }
 
 /* scores only, all heads (used by tests that need just Eq. 4 at larger sizes) */

@@ -36,6 +36,9 @@ MUTANTS = [
     ("pivotal_without_half", "o[c] = ((double)xc[c] + 0.5 * o[c]) / (double)(n + 1);", "o[c] = ((double)xc[c] + o[c]) / (double)(n + 1);"),
     ("pivotal_drops_closest", "else if (mode == 2) o[c] += ((double)xe[c] + (double)xc[c]);", "else if (mode == 2) o[c] += ((double)xe[c]);"),
     ("weighted_ignores_similarity", "else o[c] += (double)xe[c] * sim[e];", "else o[c] += (double)xe[c];"),
+    ("literal_rule_refuses_small_budgets", "if (rule == 0 && B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;",
+     "if (B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;"),
+    ("ratio_truncates", "const int N = (int)floor(alpha_important * (double)L + 0.5);", "const int N = (int)floor(alpha_important * (double)L);"),
     ("values_not_merged", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, mode, v_out", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, 0, v_out"),
 ]
 

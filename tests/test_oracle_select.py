@@ -130,3 +130,73 @@ def test_error_codes():
     with pytest.raises(oracle.OracleError) as e:
         oracle.select(s, mask, budget=4, recent_window=2)   # 3 text + 2 recent = 5 > 4
     assert e.value.code == oracle.ERR_BUDGET_BELOW_PROTECTED
+
+
+# ---- Eq. 8 taken literally (any budget), and the ratio form of the budget ------------------------------
+
+def top_text_only(scores, mask, B, M):
+    """Below |T u R|: the window, and the N = B - M best text tokens outside it; no image token."""
+    L = len(scores)
+    text = [j for j in range(L - M) if mask[j] == 0]
+    text.sort(key=lambda j: (-scores[j], j))
+    return np.array(sorted(text[: B - M] + list(range(L - M, L))), np.int32)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_literal_rule_equals_the_protecting_rule_when_text_fits(seed):
+    rng = np.random.default_rng(100 + seed)
+    L = int(rng.integers(5, 200))
+    M = int(rng.integers(0, L // 3 + 1))
+    mask = (rng.random(L) < 0.6).astype(np.uint8)
+    scores = rng.random(L) + 1e-3
+    P = oracle.protected_count(mask, M)
+    for B in sorted({P, (P + L) // 2, L}):
+        a = oracle.select(scores, mask, B, M, "protect_text")
+        b = oracle.select(scores, mask, B, M, "literal")
+        assert a[0].tolist() == b[0].tolist() and a[1].tolist() == b[1].tolist()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_literal_rule_below_the_protected_count(seed):
+    rng = np.random.default_rng(200 + seed)
+    L = int(rng.integers(8, 300))
+    M = int(rng.integers(0, L // 4 + 1))
+    mask = (rng.random(L) < 0.5).astype(np.uint8)
+    scores = np.round(rng.random(L) * 8) / 8 + 0.125 if seed % 2 else rng.random(L) + 1e-3   # odd seeds: many ties
+    P = oracle.protected_count(mask, M)
+    prev = None
+    for B in range(M, L + 1):
+        kept, ev = oracle.select(scores, mask, B, M, "literal")
+        assert len(kept) == B and sorted(set(kept.tolist()) | set(ev.tolist())) == list(range(L))
+        assert set(range(L - M, L)) <= set(kept.tolist())
+        if B < P:
+            assert kept.tolist() == top_text_only(scores, mask, B, M).tolist()
+            assert all(mask[j] == 0 or j >= L - M for j in kept)
+            with pytest.raises(oracle.OracleError):
+                oracle.select(scores, mask, B, M, "protect_text")
+        if prev is not None:
+            assert set(prev) < set(kept.tolist())            # one more place never drops a token
+        prev = kept.tolist()
+
+
+def test_literal_rule_hand_example():
+    #                 0    1    2    3    4    5     6     7
+    s = np.array([5.0, 1.0, 4.0, 2.0, 3.0, 0.5, 0.25, 9.0])
+    m = np.array([0, 1, 0, 1, 0, 1, 1, 1], np.uint8)       # text at 0, 2, 4; window = position 7
+    assert oracle.select(s, m, 3, 1, "literal")[0].tolist() == [0, 2, 7]     # N = 2 of three text tokens
+    assert oracle.select(s, m, 4, 1, "literal")[0].tolist() == [0, 2, 4, 7]
+    assert oracle.select(s, m, 5, 1, "literal")[0].tolist() == [0, 2, 3, 4, 7]   # then the best image token
+    assert oracle.select(s, m, 1, 1, "literal")[0].tolist() == [7]
+
+
+def test_budget_from_ratios():
+    assert oracle.budget_from_ratios(1000, 0.1, 0.1) == (100, 200)
+    assert oracle.budget_from_ratios(12644, 0.0, 0.05) == (0, 632)
+    with pytest.raises(oracle.OracleError):
+        oracle.budget_from_ratios(7, 0.5, 0.5)              # 4 + 4 > 7
+    with pytest.raises(oracle.OracleError):
+        oracle.budget_from_ratios(100, 1.5, 0.0)
+    for L in (1, 17, 4096, 12644):
+        for a1, a2 in ((0.01, 0.04), (0.1, 0.1), (0.0, 0.99), (0.3, 0.5)):
+            M, S = oracle.budget_from_ratios(L, a1, a2)
+            assert abs(M - a1 * L) <= 0.5 and abs((S - M) - a2 * L) <= 0.5 and 0 <= M <= S <= L
