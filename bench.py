@@ -51,7 +51,7 @@ def algorithmic_work(w: W.Workload) -> dict:
 
 def stack(args) -> int:
     """The full 7B-shaped stack: 32 layers x 4 ragged prompts (4K, 6K, 9K, 12K tokens), weighted merging.  A step is
-    the compression of all 128 (prompt, layer) caches, one lookm_compress call each, on one stream.  Inputs are drawn
+    the compression of all 128 (prompt, layer) caches by ONE lookm_compress_batch call on one stream.  Inputs are drawn
     on the GPU with a seeded generator (same recipe as the host generator) and all stay resident (about 25 GB)."""
     dev = torch.device("cuda:0")
     prompts = W.stack_prompts()
@@ -65,10 +65,10 @@ def stack(args) -> int:
             q, k, v, mask = W.generate_on_device(w, layer, dev)
             jobs.append((w, B, q, k, v, mask, out, ws))
     torch.cuda.synchronize()
+    batch = [lookm.make_job(q, k, v, mask, B, w.M, "weighted", out, ws) for w, B, q, k, v, mask, out, ws in jobs]
 
     def step():
-        for w, B, q, k, v, mask, out, ws in jobs:
-            lookm.lookm_compress(q, k, v, mask, B, w.M, "weighted", out=out, workspace=ws, check=False)
+        lookm.lookm_compress_batch(batch)
 
     for _ in range(args.warmup):
         step()

@@ -62,6 +62,16 @@ typedef enum {
 
 typedef enum { LOOKM_F32 = 0, LOOKM_BF16 = 1 } lookm_dtype;
 
+typedef enum {
+    /* text tokens and the recent window are always conserved; a budget below |T u R| is an error */
+    LOOKM_SELECT_PROTECT_TEXT = 0,
+    /* Eq. 5 and Eq. 8 exactly as printed, for any recent_window <= budget <= L: the N = budget - recent_window
+     * places before the window go to the highest boosted scores; when they cannot hold every text token, the
+     * text tokens compete for them by score and no image token is conserved.  Same result as
+     * LOOKM_SELECT_PROTECT_TEXT whenever that rule accepts the budget. */
+    LOOKM_SELECT_LITERAL = 1
+} lookm_select_rule;
+
 /* Library version string, static storage. */
 const char* lookm_version(void);
 
@@ -173,6 +183,54 @@ int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_
                        void* k_out, void* v_out, int32_t* kept_idx,
                        float* scores_out, int32_t* status_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* ---- paper-style budgets, the literal form of Eq. 8, several layers / prompts in one call --------------------- */
+
+/*
+ * Host helper for the budgets of Section 4 ("Implementation Details"): recent window M = alpha_recent * L,
+ * important tokens N = alpha_important * L (each rounded to nearest), cache size S = N + M (Eq. 8).
+ * Writes *recent_window = M and *budget = S.  LOOKM_ERR_INVALID_ARG for a ratio outside [0, 1] or a null
+ * pointer, LOOKM_ERR_BUDGET_RANGE when M + N > L.  With text-heavy prompts such budgets fall below |T u R|:
+ * use them with LOOKM_SELECT_LITERAL.
+ */
+int lookm_budget_from_ratios(int L, double alpha_recent, double alpha_important, int* recent_window, int* budget);
+
+/* lookm_select under a chosen rule (lookm_select itself is LOOKM_SELECT_PROTECT_TEXT). */
+int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L,
+                       int budget, int recent_window, lookm_select_rule rule,
+                       int32_t* kept_idx, int32_t* evicted_idx, int32_t* status_out, void* hip_stream);
+
+/*
+ * One compression job: the arguments of lookm_compress, plus the selection rule and an optional row
+ * log-sum-exp (NULL = compute it; see lookm_scores_lse).  All pointers as documented for lookm_compress.
+ */
+typedef struct lookm_job {
+    const void* q;
+    const void* k;
+    const void* v;
+    const uint8_t* modality_mask;
+    const float* row_lse;            /* device [H, L] or NULL */
+    int H, L, d;
+    lookm_dtype dt;
+    int budget, recent_window;
+    lookm_merge_mode merge_mode;
+    lookm_select_rule rule;
+    void* k_out;
+    void* v_out;
+    int32_t* kept_idx;
+    float* scores_out;               /* or NULL */
+    int32_t* status_out;             /* one word per job (jobs may not share it) */
+    void* workspace;                 /* jobs of one call run one after the other on the stream and may share it */
+    size_t workspace_bytes;
+} lookm_job;
+
+/*
+ * The whole path for n_jobs (prompt, layer) pairs - e.g. the 32 layers of each prompt of a batch, of
+ * different lengths - enqueued in order on one stream.  EVERY job is validated before the first launch:
+ * on an invalid job nothing is enqueued, the return value is that job's error and *bad_job (if not NULL)
+ * its index.  n_jobs = 0 is a no-op.
+ */
+int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream);
 
 /* ---- measurement aid ------------------------------------------------------------------------------- */
 

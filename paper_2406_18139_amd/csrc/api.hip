@@ -3,6 +3,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <cmath>
 
 namespace {
 
@@ -125,18 +126,39 @@ int lookm_scores_lse(const void* q, const void* k, const float* row_lse, int H, 
     return scores_impl(q, k, row_lse, H, L, d, dt, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
-int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L, int budget, int recent_window,
-                 int32_t* kept_idx, int32_t* evicted_idx, int32_t* status_out, void* hip_stream)
+int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L, int budget,
+                       int recent_window, lookm_select_rule rule, int32_t* kept_idx, int32_t* evicted_idx,
+                       int32_t* status_out, void* hip_stream)
 {
     if (!scores || !modality_mask || !status_out) return LOOKM_ERR_INVALID_ARG;
     if (H <= 0 || L <= 0) return LOOKM_ERR_INVALID_ARG;
+    if ((int)rule < LOOKM_SELECT_PROTECT_TEXT || (int)rule > LOOKM_SELECT_LITERAL) return LOOKM_ERR_INVALID_ARG;
     if (L > LOOKM_MAX_L) return LOOKM_ERR_UNSUPPORTED;
     int rc = check_budget(L, budget, recent_window);
     if (rc != LOOKM_OK) return rc;
     // an empty list (budget 0, or budget L) may be passed as NULL
     if ((budget > 0 && !kept_idx) || (budget < L && !evicted_idx)) return LOOKM_ERR_INVALID_ARG;
-    return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted_idx,
-                                     status_out, (hipStream_t)hip_stream);
+    return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, (int)rule, kept_idx,
+                                     evicted_idx, status_out, (hipStream_t)hip_stream);
+}
+
+int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L, int budget, int recent_window,
+                 int32_t* kept_idx, int32_t* evicted_idx, int32_t* status_out, void* hip_stream)
+{
+    return lookm_select_rule_(scores, modality_mask, H, L, budget, recent_window, LOOKM_SELECT_PROTECT_TEXT, kept_idx,
+                              evicted_idx, status_out, hip_stream);
+}
+
+int lookm_budget_from_ratios(int L, double alpha_recent, double alpha_important, int* recent_window, int* budget)
+{
+    if (L <= 0 || !recent_window || !budget) return LOOKM_ERR_INVALID_ARG;
+    if (!(alpha_recent >= 0.0 && alpha_recent <= 1.0) || !(alpha_important >= 0.0 && alpha_important <= 1.0))
+        return LOOKM_ERR_INVALID_ARG;
+    const long M = (long)std::floor(alpha_recent * (double)L + 0.5), N = (long)std::floor(alpha_important * (double)L + 0.5);
+    if (M + N > (long)L) return LOOKM_ERR_BUDGET_RANGE;
+    *recent_window = (int)M;
+    *budget = (int)(M + N);
+    return LOOKM_OK;
 }
 
 int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted_idx, int H, int L, int d,
@@ -177,49 +199,70 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
                                     at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
 }
 
-static int compress_impl(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
-                         const float* row_lse, int H, int L, int d, lookm_dtype dt, int budget, int recent_window,
-                         lookm_merge_mode merge_mode, void* k_out, void* v_out, int32_t* kept_idx, float* scores_out,
-                         int32_t* status_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+// everything the host can check about one job, without touching the device
+static int validate_job(const lookm_job& j)
 {
-    if (!q || !k || !v || !modality_mask || !status_out) return LOOKM_ERR_INVALID_ARG;
-    if (budget > 0 && (!k_out || !v_out || !kept_idx)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
-    if ((int)merge_mode < LOOKM_MERGE_NONE || (int)merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
-    int rc = check_shape(H, L, d, (int)dt);
+    if (!j.q || !j.k || !j.v || !j.modality_mask || !j.status_out) return LOOKM_ERR_INVALID_ARG;
+    if (j.budget > 0 && (!j.k_out || !j.v_out || !j.kept_idx)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
+    if ((int)j.merge_mode < LOOKM_MERGE_NONE || (int)j.merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
+    if ((int)j.rule < LOOKM_SELECT_PROTECT_TEXT || (int)j.rule > LOOKM_SELECT_LITERAL) return LOOKM_ERR_INVALID_ARG;
+    int rc = check_shape(j.H, j.L, j.d, (int)j.dt);
     if (rc != LOOKM_OK) return rc;
-    rc = check_budget(L, budget, recent_window);
+    rc = check_budget(j.L, j.budget, j.recent_window);
     if (rc != LOOKM_OK) return rc;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out) ||
-        (scores_out && !aligned16(scores_out)))
+    if (!aligned16(j.q) || !aligned16(j.k) || !aligned16(j.v) || !aligned16(j.k_out) || !aligned16(j.v_out) ||
+        (j.scores_out && !aligned16(j.scores_out)) || (j.row_lse && !aligned16(j.row_lse)))
         return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
-    if (rc != LOOKM_OK) return rc;
+    return check_workspace(j.workspace, j.workspace_bytes, j.H, j.L, j.d, (int)j.dt, j.budget);
+}
 
+// the launch sequence of one validated job
+static int enqueue_job(const lookm_job& j, hipStream_t st)
+{
+    const int H = j.H, L = j.L, d = j.d, budget = j.budget;
+    const lookm_dtype dt = j.dt;
+    void* workspace = j.workspace;
     const Layout w = make_layout(H, L, d, (int)dt, budget);
-    hipStream_t st = (hipStream_t)hip_stream;
-    float* scores = scores_out ? scores_out : at<float>(workspace, w.scores);
+    float* scores = j.scores_out ? j.scores_out : at<float>(workspace, w.scores);
     int32_t* evicted = at<int32_t>(workspace, w.evicted);
     int32_t* assign = at<int32_t>(workspace, w.assign);
     float* sim = at<float>(workspace, w.sim);
 
     // the matching needs the inverse key norms; the matrix-core score pass writes them from the key rows it holds
-    const bool match = merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
+    const bool match = j.merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
     float* rnorm = at<float>(workspace, w.rnorm);
-    rc = lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores,
-                                   match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
+    int rc = lookm_host::launch_scores(j.q, j.k, H, L, d, dt, at<float>(workspace, w.lse), j.row_lse, scores,
+                                       match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
-    rc = lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, kept_idx, evicted, status_out, st);
+    rc = lookm_host::launch_select(scores, j.modality_mask, H, L, budget, j.recent_window, (int)j.rule, j.kept_idx,
+                                   evicted, j.status_out, st);
     if (rc != LOOKM_OK) return rc;
-    if (merge_mode != LOOKM_MERGE_NONE && budget < L) {
+    if (j.merge_mode != LOOKM_MERGE_NONE && budget < L) {
         if (budget == 0) return LOOKM_OK;   // nothing conserved: nothing to merge into
-        rc = lookm_host::launch_nearest(k, kept_idx, evicted, H, L, d, dt, budget, rnorm,
+        rc = lookm_host::launch_nearest(j.k, j.kept_idx, evicted, H, L, d, dt, budget, rnorm,
                                         lookm_host::scores_write_rnorm(d, dt), assign, sim,
                                         at<void>(workspace, w.partials), st);
         if (rc != LOOKM_OK) return rc;
     }
-    return lookm_host::launch_merge(k, v, kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)merge_mode,
+    return lookm_host::launch_merge(j.k, j.v, j.kept_idx, evicted, assign, sim, H, L, d, dt, budget, (int)j.merge_mode,
                                     at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
-                                    at<float>(workspace, w.member_w), k_out, v_out, st);
+                                    at<float>(workspace, w.member_w), j.k_out, j.v_out, st);
+}
+
+static int compress_impl(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
+                         const float* row_lse, int H, int L, int d, lookm_dtype dt, int budget, int recent_window,
+                         lookm_merge_mode merge_mode, void* k_out, void* v_out, int32_t* kept_idx, float* scores_out,
+                         int32_t* status_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    lookm_job j;
+    j.q = q; j.k = k; j.v = v; j.modality_mask = modality_mask; j.row_lse = row_lse;
+    j.H = H; j.L = L; j.d = d; j.dt = dt;
+    j.budget = budget; j.recent_window = recent_window; j.merge_mode = merge_mode; j.rule = LOOKM_SELECT_PROTECT_TEXT;
+    j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
+    j.workspace = workspace; j.workspace_bytes = workspace_bytes;
+    const int rc = validate_job(j);
+    if (rc != LOOKM_OK) return rc;
+    return enqueue_job(j, (hipStream_t)hip_stream);
 }
 
 int lookm_compress(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L, int d,
@@ -239,6 +282,26 @@ int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_
     if (!row_lse) return LOOKM_ERR_INVALID_ARG;
     return compress_impl(q, k, v, modality_mask, row_lse, H, L, d, dt, budget, recent_window, merge_mode, k_out, v_out,
                          kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
+}
+
+int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream)
+{
+    if (n_jobs < 0 || (n_jobs > 0 && !jobs)) return LOOKM_ERR_INVALID_ARG;
+    for (int i = 0; i < n_jobs; ++i) {
+        const int rc = validate_job(jobs[i]);
+        if (rc != LOOKM_OK) {
+            if (bad_job) *bad_job = i;
+            return rc;
+        }
+    }
+    for (int i = 0; i < n_jobs; ++i) {
+        const int rc = enqueue_job(jobs[i], (hipStream_t)hip_stream);
+        if (rc != LOOKM_OK) {                 // only a failing HIP runtime call can end up here
+            if (bad_job) *bad_job = i;
+            return rc;
+        }
+    }
+    return LOOKM_OK;
 }
 
 int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,

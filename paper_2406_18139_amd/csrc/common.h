@@ -80,7 +80,7 @@ int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype
                   float* scores, float* rnorm, float* scratch, hipStream_t st);
 inline bool scores_write_rnorm(int d, lookm_dtype dt) { return dt == LOOKM_BF16 && d == 128; }
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
-int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
+int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int rule, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st);
 // rnorm_ready: rnorm already holds the inverse key norms (written by launch_scores)
 int launch_nearest(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int d, lookm_dtype dt,

@@ -52,13 +52,13 @@ __device__ __forceinline__ int wave_scan_excl(int wave_value, int* wtot, int& to
 // inside the wave plus one 16-entry scan across waves.
 template <int IPT>
 __global__ void __launch_bounds__(SEL_THREADS)
-k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int L, int B, int M,
+k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int L, int B, int M, int rule,
          int32_t* __restrict__ kept, int32_t* __restrict__ evicted, int32_t* __restrict__ status)
 {
     __shared__ int hist[SEL_BINS];
     __shared__ uint32_t cand[SEL_CAND];     // keys that share the threshold's top 12 bits
     __shared__ int wtot[8][SEL_WAVES];      // one row per workgroup-wide scan
-    __shared__ uint32_t wmin[SEL_WAVES], wmax[SEL_WAVES];
+    __shared__ uint32_t wmin[SEL_WAVES], wmax[SEL_WAVES], wtmin[SEL_WAVES], wtmax[SEL_WAVES];
     __shared__ int sh_bin, sh_k, sh_ncand;
     __shared__ uint32_t sh_thr;
 
@@ -81,48 +81,53 @@ k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) hist[i] = 0;
     if (tid == 0) sh_ncand = 0;
 
-    uint32_t prot_m = 0, evic_m = 0;   // bit i: position seg + i*64 + lane is protected / evictable
-    uint32_t kmin = 0xffffffffu, kmax = 0u;
-    int nprot_wave = 0;
+    // bit i of each mask: position seg + i*64 + lane is in the recent window / a text token before it / an image
+    // token before it
+    uint32_t win_m = 0, text_m = 0, img_m = 0;
+    uint32_t kmin = 0xffffffffu, kmax = 0u;       // over the image tokens before the window
+    uint32_t tmin = 0xffffffffu, tmax = 0u;       // over the text tokens before the window (literal rule only)
+    int ntext_wave = 0;
 #pragma unroll
     for (int i = 0; i < IPT; ++i) {
         const int j = seg + i * 64 + lane;
-        bool prot = false;
+        bool text = false;
         if (j < L) {
-            prot = (img[i] == 0 || j >= head_len);
-            if (prot) prot_m |= 1u << i;
-            else {
-                evic_m |= 1u << i;
-                key[i] = score_key(__uint_as_float(key[i]));
+            key[i] = score_key(__uint_as_float(key[i]));
+            if (j >= head_len) win_m |= 1u << i;
+            else if (img[i] == 0) {
+                text = true;
+                text_m |= 1u << i;
+                if (rule == LOOKM_SELECT_LITERAL) { tmin = min(tmin, key[i]); tmax = max(tmax, key[i]); }
+            } else {
+                img_m |= 1u << i;
                 kmin = min(kmin, key[i]);
                 kmax = max(kmax, key[i]);
             }
         }
-        nprot_wave += __popcll(__ballot(prot));
+        ntext_wave += __popcll(__ballot(text));
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, off));
         kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, off));
     }
-    if (lane == 0) { wmin[wave] = kmin; wmax[wave] = kmax; }
-
-    int nprot;   // |T u R|
-    wave_scan_excl(nprot_wave, wtot[0], nprot);
+    if (rule == LOOKM_SELECT_LITERAL) {
 #pragma unroll
-    for (int w = 0; w < SEL_WAVES; ++w) { kmin = min(kmin, wmin[w]); kmax = max(kmax, wmax[w]); }
-    // Scores of a head crowd into a few binades, so the raw top bits would send most keys to a handful of
-    // histogram bins.  Keys are re-based to the head's own range [kmin, kmax] and shifted up to use all 32
-    // bits: order and equality are unchanged, the first digit spreads over the bins, and few keys are left
-    // to tell apart after it.
-    {
-        const uint32_t range = (kmax >= kmin) ? kmax - kmin : 0u;
-        const int lz = range ? __clz(range) : 0;
-#pragma unroll
-        for (int i = 0; i < IPT; ++i) key[i] = (key[i] - kmin) << lz;   // only evictable entries are used below
+        for (int off = 32; off > 0; off >>= 1) {
+            tmin = min(tmin, (uint32_t)__shfl_xor((int)tmin, off));
+            tmax = max(tmax, (uint32_t)__shfl_xor((int)tmax, off));
+        }
     }
-    const int k_img = B - nprot;
-    if (k_img < 0) {
+    if (lane == 0) { wmin[wave] = kmin; wmax[wave] = kmax; wtmin[wave] = tmin; wtmax[wave] = tmax; }
+
+    int ntext;   // text tokens before the window; |T u R| = ntext + M
+    wave_scan_excl(ntext_wave, wtot[0], ntext);
+    const int nprot = ntext + M;
+    // Eq. 8 has N = B - M places before the window.  If they hold every text token, text and window are sure and
+    // the image tokens compete for the rest; if not, the default rule reports an error, while the literal rule
+    // lets the (boosted, hence always higher-ranked) text tokens compete for the N places and conserves no image.
+    const bool text_competes = (B < nprot) && (rule == LOOKM_SELECT_LITERAL);
+    if (B < nprot && !text_competes) {
         // text + window do not fit: report, and leave in-range (meaningless) index lists behind
         if (tid == 0) *status = LOOKM_ERR_BUDGET_BELOW_PROTECTED;
         for (int r = tid; r < B; r += SEL_THREADS) kept[r] = r;
@@ -130,7 +135,27 @@ k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int
         return;
     }
     if (tid == 0 && h == 0) *status = LOOKM_OK;
-    const int n_evictable = L - nprot;
+    const uint32_t prot_m = text_competes ? win_m : (win_m | text_m);   // conserved whatever the scores
+    const uint32_t evic_m = text_competes ? text_m : img_m;             // compete by score
+    const int k_img = text_competes ? B - M : B - nprot;                // places they compete for
+    const int n_evictable = text_competes ? ntext : L - nprot;
+    kmin = 0xffffffffu;
+    kmax = 0u;
+#pragma unroll
+    for (int w = 0; w < SEL_WAVES; ++w) {
+        kmin = min(kmin, text_competes ? wtmin[w] : wmin[w]);
+        kmax = max(kmax, text_competes ? wtmax[w] : wmax[w]);
+    }
+    // Scores of a head crowd into a few binades, so the raw top bits would send most keys to a handful of
+    // histogram bins.  Keys are re-based to the competing tokens' own range [kmin, kmax] and shifted up to use
+    // all 32 bits: order and equality are unchanged, the first digit spreads over the bins, and few keys are
+    // left to tell apart after it.
+    {
+        const uint32_t range = (kmax >= kmin) ? kmax - kmin : 0u;
+        const int lz = range ? __clz(range) : 0;
+#pragma unroll
+        for (int i = 0; i < IPT; ++i) key[i] = (key[i] - kmin) << lz;   // only competing entries are used below
+    }
     const bool keep_all = (k_img == n_evictable), keep_none = (k_img == 0);
 
     // key of the k_img-th largest evictable score, and how many keys equal to it to take
@@ -274,19 +299,19 @@ k_select(const float* __restrict__ scores, const uint8_t* __restrict__ mask, int
 
 namespace lookm_host {
 
-int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int32_t* kept,
+int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int rule, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st)
 {
     const int per_thread = (L + lookm::SEL_THREADS - 1) / lookm::SEL_THREADS;
     dim3 grid(H), block(lookm::SEL_THREADS);
     if (per_thread <= 4)
-        hipLaunchKernelGGL(lookm::k_select<4>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+        hipLaunchKernelGGL(lookm::k_select<4>, grid, block, 0, st, scores, mask, L, budget, M, rule, kept, evicted, status);
     else if (per_thread <= 8)
-        hipLaunchKernelGGL(lookm::k_select<8>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+        hipLaunchKernelGGL(lookm::k_select<8>, grid, block, 0, st, scores, mask, L, budget, M, rule, kept, evicted, status);
     else if (per_thread <= 16)
-        hipLaunchKernelGGL(lookm::k_select<16>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+        hipLaunchKernelGGL(lookm::k_select<16>, grid, block, 0, st, scores, mask, L, budget, M, rule, kept, evicted, status);
     else if (per_thread <= 32)
-        hipLaunchKernelGGL(lookm::k_select<32>, grid, block, 0, st, scores, mask, L, budget, M, kept, evicted, status);
+        hipLaunchKernelGGL(lookm::k_select<32>, grid, block, 0, st, scores, mask, L, budget, M, rule, kept, evicted, status);
     else
         return LOOKM_ERR_UNSUPPORTED;
     mark(LOOKM_K_SELECT);

@@ -27,13 +27,27 @@ ERR_DEVICE = -6
 
 MERGE_MODES = {"none": 0, "averaged": 1, "pivotal": 2, "weighted": 3}
 F32, BF16 = 0, 1
+SELECT_RULES = {"protect_text": 0, "literal": 1}
 
 EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
-           "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse"]
+           "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
+           "lookm_select_rule_", "lookm_compress_batch"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
+
+
+class Job(ctypes.Structure):
+    """struct lookm_job of include/lookm.h, field for field."""
+    _fields_ = [("q", ctypes.c_void_p), ("k", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("modality_mask", ctypes.c_void_p), ("row_lse", ctypes.c_void_p),
+                ("H", ctypes.c_int), ("L", ctypes.c_int), ("d", ctypes.c_int), ("dt", ctypes.c_int),
+                ("budget", ctypes.c_int), ("recent_window", ctypes.c_int), ("merge_mode", ctypes.c_int),
+                ("rule", ctypes.c_int),
+                ("k_out", ctypes.c_void_p), ("v_out", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
+                ("scores_out", ctypes.c_void_p), ("status_out", ctypes.c_void_p),
+                ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
 
 
 class LookmError(RuntimeError):
@@ -78,6 +92,12 @@ def lib() -> ctypes.CDLL:
         L.lookm_nearest.argtypes = [vp, vp, vp, I, I, I, I, I, vp, vp, vp, sz, vp]
         L.lookm_merge.restype = I
         L.lookm_merge.argtypes = [vp, vp, vp, vp, vp, vp, I, I, I, I, I, I, vp, vp, vp, sz, vp]
+        L.lookm_budget_from_ratios.restype = I
+        L.lookm_budget_from_ratios.argtypes = [I, ctypes.c_double, ctypes.c_double, ctypes.POINTER(I), ctypes.POINTER(I)]
+        L.lookm_select_rule_.restype = I
+        L.lookm_select_rule_.argtypes = [vp, vp, I, I, I, I, I, vp, vp, vp, vp]
+        L.lookm_compress_batch.restype = I
+        L.lookm_compress_batch.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(I), vp]
         _lib = L
     return _lib
 
@@ -112,6 +132,20 @@ def _stream() -> int:
 
 def _mode(m) -> int:
     return MERGE_MODES[m] if isinstance(m, str) else int(m)
+
+
+def _rule(r) -> int:
+    return SELECT_RULES[r] if isinstance(r, str) else int(r)
+
+
+def budget_from_ratios(L: int, alpha_recent: float, alpha_important: float):
+    """lookm_budget_from_ratios -> (recent_window, budget)."""
+    M, B = ctypes.c_int(0), ctypes.c_int(0)
+    rc = lib().lookm_budget_from_ratios(int(L), float(alpha_recent), float(alpha_important), ctypes.byref(M),
+                                        ctypes.byref(B))
+    if rc != OK:
+        raise LookmError(rc, "lookm_budget_from_ratios")
+    return M.value, B.value
 
 
 def protected_count(mask_host, recent_window: int) -> int:
@@ -152,10 +186,24 @@ class Compressed:
 def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode,
                    want_scores: bool = False, out: Optional[Compressed] = None,
                    workspace: Optional[torch.Tensor] = None, check: bool = True,
-                   row_lse: Optional[torch.Tensor] = None) -> Compressed:
+                   row_lse: Optional[torch.Tensor] = None, rule="protect_text") -> Compressed:
     """One layer's compression.  q, k, v: GPU tensors [H, L, d]; modality_mask: GPU uint8 [L].
     ``check=True`` synchronises to read the device status word and raises on failure.
-    With ``row_lse`` (GPU float32 [H, L]) the call forwards to lookm_compress_lse."""
+    With ``row_lse`` (GPU float32 [H, L]) the call forwards to lookm_compress_lse; with a selection rule other
+    than the default it forwards to lookm_compress_batch as a single job (the entry point that takes a rule)."""
+    if _rule(rule) != 0:
+        H, L, d = q.shape
+        if out is None:
+            out = alloc_outputs(H, L, d, int(budget), q.dtype, q.device, want_scores)
+        if workspace is None:
+            workspace = alloc_workspace(H, L, d, min(max(int(budget), 0), L), _dt(q), q.device)
+        lookm_compress_batch([make_job(q, k, v, modality_mask, budget, recent_window, merge_mode, out, workspace,
+                                       row_lse=row_lse, rule=rule)])
+        if check:
+            st = int(out.status.item())
+            if st != OK:
+                raise LookmError(st, "lookm_compress_batch (device)")
+        return out
     H, L, d = q.shape
     dt = _dt(q)
     B = int(budget)
@@ -183,6 +231,30 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
         if st != OK:
             raise LookmError(st, "lookm_compress (device)")
     return out
+
+
+def make_job(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode, out: Compressed,
+             workspace: torch.Tensor, row_lse: Optional[torch.Tensor] = None, rule="protect_text") -> Job:
+    """A struct lookm_job over the given tensors (which the caller keeps alive until the work has run)."""
+    H, L, d = q.shape
+    if row_lse is not None and (row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (H, L)):
+        raise ValueError("row_lse must be float32 [H, L]")
+    wp, wn = _ws_ptr(workspace)
+    return Job(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
+               _dev(row_lse, "row_lse") if row_lse is not None else None, H, L, d, _dt(q), int(budget),
+               int(recent_window), _mode(merge_mode), _rule(rule), _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"),
+               _dev(out.kept_idx, "kept_idx"), _dev(out.scores, "scores") if out.scores is not None else None,
+               _dev(out.status, "status"), wp, wn)
+
+
+def lookm_compress_batch(jobs) -> None:
+    """lookm_compress_batch over a list of Job structs (see make_job), on the current stream."""
+    n = len(jobs)
+    arr = (Job * max(n, 1))(*jobs)
+    bad = ctypes.c_int(-1)
+    rc = lib().lookm_compress_batch(arr, n, ctypes.byref(bad), _stream())
+    if rc != OK:
+        raise LookmError(rc, f"lookm_compress_batch (job {bad.value})")
 
 
 def alloc_outputs(H: int, L: int, d: int, budget: int, dtype, device, want_scores: bool = False) -> Compressed:
@@ -241,15 +313,20 @@ def lookm_scores_lse(q, k, row_lse, workspace: Optional[torch.Tensor] = None) ->
     return scores
 
 
-def lookm_select(scores, modality_mask, budget: int, recent_window: int, check: bool = True):
+def lookm_select(scores, modality_mask, budget: int, recent_window: int, check: bool = True, rule="protect_text"):
     H, L = scores.shape
     B = int(budget)
     dev = scores.device
     kept = torch.empty((H, max(B, 0)), dtype=torch.int32, device=dev)
     evicted = torch.empty((H, max(L - B, 0)), dtype=torch.int32, device=dev)
     status = torch.zeros(1, dtype=torch.int32, device=dev)
-    rc = lib().lookm_select(_dev(scores, "scores"), _dev(modality_mask, "modality_mask"), H, L, B,
-                            int(recent_window), kept.data_ptr(), evicted.data_ptr(), status.data_ptr(), _stream())
+    if _rule(rule) == 0:
+        rc = lib().lookm_select(_dev(scores, "scores"), _dev(modality_mask, "modality_mask"), H, L, B,
+                                int(recent_window), kept.data_ptr(), evicted.data_ptr(), status.data_ptr(), _stream())
+    else:
+        rc = lib().lookm_select_rule_(_dev(scores, "scores"), _dev(modality_mask, "modality_mask"), H, L, B,
+                                      int(recent_window), _rule(rule), kept.data_ptr(), evicted.data_ptr(),
+                                      status.data_ptr(), _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_select")
     if check:

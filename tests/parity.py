@@ -37,20 +37,23 @@ def check_scores(gpu_scores: np.ndarray, ref: np.ndarray, rtol=SCORE_RTOL):
     return float(rel.max())
 
 
-def check_kept(kept_gpu, scores_gpu, ref_scores, ref_kept, mask, B, M):
+def check_kept(kept_gpu, scores_gpu, ref_scores, ref_kept, mask, B, M, rule="protect_text"):
     """Returns the number of heads whose kept set differs from the fp64 oracle's (all inside the tie band)."""
     H = kept_gpu.shape[0]
     differing = 0
     for h in range(H):
         # both sides deciding on the kernel's scores: must be identical
-        kp, _ = oracle.select(scores_gpu[h].astype(np.float64), mask, B, M)
+        kp, _ = oracle.select(scores_gpu[h].astype(np.float64), mask, B, M, rule)
         assert kp.tolist() == kept_gpu[h].tolist(), f"head {h}: selection differs from the oracle on the kernel's own scores"
         if kept_gpu[h].tolist() != ref_kept[h].tolist():
             differing += 1
             a, b = set(kept_gpu[h].tolist()), set(ref_kept[h].tolist())
             sym = sorted(a ^ b)
-            kept_img = [j for j in ref_kept[h] if mask[j] == 1 and j < len(mask) - M]
-            thr = min(ref_scores[h][j] for j in kept_img)
+            # the tokens that competed by score: image tokens before the window, or, under the literal rule
+            # with a budget below the protected count, text tokens before the window
+            competing = 1 if B >= oracle.protected_count(mask, M) else 0
+            kept_cmp = [j for j in ref_kept[h] if mask[j] == competing and j < len(mask) - M]
+            thr = min(ref_scores[h][j] for j in kept_cmp)
             for j in sym:
                 rel = abs(ref_scores[h][j] - thr) / thr
                 assert rel <= TIE_SCORE, f"head {h}: position {j} differs outside the tie band (rel {rel:.2e})"
@@ -82,14 +85,14 @@ def check_merge(x_head_f32, kept, evicted, assign, sim, mode, out_gpu, dtype):
     return float(err.max())
 
 
-def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None):
+def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None, M=None, rule="protect_text"):
     """Full path on the GPU for workload ``w`` (all heads, or ``heads``), oracle on ``oracle_heads``
     (indices into the generated heads; default all).  Returns a dict of statistics."""
     q, k, v, mask = __import__("paper_2406_18139_amd.workloads", fromlist=["generate"]).generate(w, layer, heads)
     B = w.budget() if B is None else B
-    M = w.M
+    M = w.M if M is None else M
     qg, kg, vg, mg = to_gpu(q, k, v, mask)
-    res = lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, want_scores=True)
+    res = lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, want_scores=True, rule=rule)
     torch.cuda.synchronize()
     kept_g = res.kept_idx.cpu().numpy()
     scores_g = res.scores.cpu().numpy()
@@ -99,6 +102,10 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None):
     assert kept_g.shape == (H, B)
     assert np.all(np.diff(kept_g, axis=1) > 0) and kept_g.min() >= 0 and kept_g.max() < L
     prot = np.flatnonzero((mask_np == 0) | (np.arange(L) >= L - M))
+    if B < len(prot):                      # literal rule below the protected count: only the window is sure,
+        prot = np.arange(L - M, L)         # and no image token before it may be conserved
+        for h in range(H):
+            assert not np.any(mask_np[kept_g[h][kept_g[h] < L - M]] == 1), f"head {h}: an image token was conserved"
     for h in range(H):
         assert np.isin(prot, kept_g[h]).all(), f"head {h}: a protected position was evicted"
     np.testing.assert_allclose(scores_g.astype(np.float64).sum(1), L, rtol=2e-5)
@@ -121,9 +128,9 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None):
     ref_scores = oracle.scores(q[oh], k[oh])
     for n, h in enumerate(oh):
         stats["score_relerr"] = max(stats["score_relerr"], check_scores(scores_g[h].astype(np.float64), ref_scores[n]))
-        ref_kept, _ = oracle.select(ref_scores[n], mask_np, B, M)
+        ref_kept, _ = oracle.select(ref_scores[n], mask_np, B, M, rule)
         stats["kept_diff_heads"] += check_kept(kept_g[h:h + 1], scores_g[h:h + 1], ref_scores[n:n + 1], ref_kept[None],
-                                               mask_np, B, M)
+                                               mask_np, B, M, rule)
         if mode != "none" and B < L:
             stats["nearest_tie_rows"] += check_nearest(kf[h], kept_g[h], ev_np[h], assign_g[h], sim_g[h])
             a, s = assign_g[h], sim_g[h]

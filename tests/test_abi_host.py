@@ -97,6 +97,51 @@ def test_stage_calls_reject_bad_arguments():
     assert L.lookm_merge(FAKE, FAKE, FAKE, None, FAKE, FAKE, 1, 8, 8, 0, 4, 1, FAKE, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
 
 
+def fake_job(**kw):
+    f = dict(q=FAKE, k=FAKE, v=FAKE, modality_mask=FAKE, row_lse=None, H=2, L=64, d=64, dt=0, budget=32, recent_window=8,
+             merge_mode=1, rule=0, k_out=FAKE, v_out=FAKE, kept_idx=FAKE, scores_out=None, status_out=FAKE,
+             workspace=FAKE, workspace_bytes=1 << 30)
+    f.update(kw)
+    return lookm.Job(**f)
+
+
+def test_batch_validates_every_job_before_any_launch():
+    import ctypes
+    L = lookm.lib()
+    bad = ctypes.c_int(-1)
+
+    def run(jobs):
+        arr = (lookm.Job * len(jobs))(*jobs)
+        return L.lookm_compress_batch(arr, len(jobs), ctypes.byref(bad), None)
+
+    assert L.lookm_compress_batch(None, 0, None, None) == lookm.OK              # nothing to do
+    assert L.lookm_compress_batch(None, 2, None, None) == lookm.ERR_INVALID_ARG
+    # every job below is invalid, so nothing is ever enqueued; the LAST job decides code and index
+    assert run([fake_job(q=None)]) == lookm.ERR_INVALID_ARG and bad.value == 0
+    assert run([fake_job(rule=5)]) == lookm.ERR_INVALID_ARG
+    assert run([fake_job(budget=99)]) == lookm.ERR_BUDGET_RANGE
+    assert run([fake_job(row_lse=FAKE + 2)]) == lookm.ERR_INVALID_ARG
+    # the struct's last field: a layout that disagreed with the header would report something else
+    assert run([fake_job(workspace_bytes=64)]) == lookm.ERR_WORKSPACE and bad.value == 0
+    assert run([fake_job(d=100), fake_job()]) == lookm.ERR_UNSUPPORTED and bad.value == 0
+
+
+def test_budget_from_ratios_matches_the_oracle():
+    import oracle
+    for L in (1, 17, 256, 4096, 12644, 32768):
+        for a1 in (0.0, 0.01, 0.1, 0.25):
+            for a2 in (0.0, 0.04, 0.1, 0.5, 0.74):
+                assert lookm.budget_from_ratios(L, a1, a2) == oracle.budget_from_ratios(L, a1, a2)
+    with pytest.raises(lookm.LookmError) as e:
+        lookm.budget_from_ratios(100, 0.6, 0.6)
+    assert e.value.code == lookm.ERR_BUDGET_RANGE
+    with pytest.raises(lookm.LookmError) as e:
+        lookm.budget_from_ratios(100, -0.1, 0.6)
+    assert e.value.code == lookm.ERR_INVALID_ARG
+    L = lookm.lib()
+    assert L.lookm_select_rule_(FAKE, FAKE, 1, 8, 4, 0, 3, FAKE, FAKE, FAKE, None) == lookm.ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 8, 8)

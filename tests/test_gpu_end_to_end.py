@@ -132,3 +132,64 @@ def test_odd_shapes_on_the_matrix_core_path(H, L, n_img, img_tokens, spans, rho,
         print(w.name, mode, st)
         assert st["kept_diff_heads"] == 0
         assert st["nearest_tie_rows"] <= max(1, 2e-3 * st["rows_matched"])
+
+
+# ---- paper-style budgets: ratios, Eq. 8 taken literally, several jobs in one call ---------------------------
+
+@pytest.mark.parametrize("mode", ["pivotal", "weighted"])
+def test_literal_rule_below_the_protected_count(mode):
+    # the tiny configuration has 128 text tokens of 256: a 20 % total budget cannot hold them
+    M, B = lookm.budget_from_ratios(W.TINY.L, 0.05, 0.15)
+    assert B < W.TINY.n_protected()
+    st = parity.run_and_check(W.TINY, mode, B=B, M=M, rule="literal")
+    print("tiny literal", mode, st)
+    assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
+    # the 7B-shaped layer under the paper's 10 % total budget (text alone is 20 % of the prompt)
+    w = W.LLAVA7B
+    M, B = lookm.budget_from_ratios(w.L, 0.01, 0.09)
+    assert B < w.n_protected()
+    st = parity.run_and_check(w, mode, heads=[0, 9, 31], B=B, M=M, rule="literal")
+    print("llava7b literal", mode, st)
+    assert st["kept_diff_heads"] <= 1
+
+
+def test_literal_rule_equals_default_rule_when_text_fits():
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w, heads=[2, 5])
+    args = (q.cuda(), k.cuda(), v.cuda(), mask.cuda(), w.budget(), w.M, "averaged")
+    a = lookm.lookm_compress(*args)
+    b = lookm.lookm_compress(*args, rule="literal")
+    assert torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out)
+
+
+def test_batch_call_equals_single_calls():
+    # three jobs of different shapes, rules and modes in one call, sharing one workspace
+    cases = [(W.TINY, None, W.TINY.budget(), W.TINY.M, "averaged", "protect_text"),
+             (W.LLAVA7B, [1, 2], W.LLAVA7B.budget(), W.LLAVA7B.M, "weighted", "protect_text"),
+             (W.LLAVA7B, [3], 290, 29, "pivotal", "literal")]
+    single, jobs, outs, keep = [], [], [], []
+    ws_bytes = 0
+    for w, heads, B, M, mode, rule in cases:
+        q, k, v, mask = W.generate(w, heads=heads)
+        qg, kg, vg, mg = q.cuda(), k.cuda(), v.cuda(), mask.cuda()
+        keep.append((qg, kg, vg, mg))
+        single.append(lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, want_scores=True, rule=rule))
+        H, L, d = q.shape
+        ws_bytes = max(ws_bytes, lookm.workspace_bytes(H, L, d, B, lookm._dt(qg)))
+    ws = torch.empty(ws_bytes + 256, dtype=torch.uint8, device="cuda")
+    for (w, heads, B, M, mode, rule), (qg, kg, vg, mg) in zip(cases, keep):
+        H, L, d = qg.shape
+        out = lookm.alloc_outputs(H, L, d, B, qg.dtype, qg.device, want_scores=True)
+        outs.append(out)
+        jobs.append(lookm.make_job(qg, kg, vg, mg, B, M, mode, out, ws, rule=rule))
+    lookm.lookm_compress_batch(jobs)
+    torch.cuda.synchronize()
+    for a, b in zip(single, outs):
+        assert int(b.status.item()) == 0
+        assert torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.scores, b.scores)
+        assert torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out)
+    # an invalid job anywhere: nothing runs, the error names it
+    bad = lookm.make_job(*keep[0], 9999, 0, "averaged", outs[0], ws)
+    with pytest.raises(lookm.LookmError) as e:
+        lookm.lookm_compress_batch([jobs[0], bad])
+    assert e.value.code == lookm.ERR_BUDGET_RANGE and "job 1" in str(e.value)

@@ -118,6 +118,31 @@ def test_select_scores_in_a_narrow_range_or_all_equal():
             assert kept[0].tolist() == rk.tolist() and ev[0].tolist() == re_.tolist(), B
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_select_literal_rule_matches_oracle_for_every_budget(seed):
+    # Eq. 8 as printed: below |T u R| the text tokens compete by score and no image token is conserved
+    rng = np.random.default_rng(40 + seed)
+    H = 2
+    L = int(rng.integers(50, 3000))
+    M = int(rng.integers(0, 40))
+    mask = (rng.random(L) < 0.5).astype(np.uint8)
+    scores = (rng.integers(1, 60, (H, L)) / 8.0 if seed % 2 else rng.random((H, L)) + 1e-3).astype(np.float32)
+    sg = torch.from_numpy(scores).cuda()
+    mg = torch.from_numpy(mask).cuda()
+    P = oracle.protected_count(mask, M)
+    budgets = sorted({M, M + 1, (M + P) // 2, P - 1, P, P + 1, (P + L) // 2, L} & set(range(M, L + 1)))
+    for B in budgets:
+        kept, ev = lookm.lookm_select(sg, mg, B, M, rule="literal")
+        kept, ev = kept.cpu().numpy(), ev.cpu().numpy()
+        for h in range(H):
+            rk, re_ = oracle.select(scores[h].astype(np.float64), mask, B, M, "literal")
+            assert kept[h].tolist() == rk.tolist() and ev[h].tolist() == re_.tolist(), (L, M, B, h)
+        if B < P:
+            with pytest.raises(lookm.LookmError) as e:
+                lookm.lookm_select(sg, mg, B, M)                     # the default rule still refuses
+            assert e.value.code == lookm.ERR_BUDGET_BELOW_PROTECTED
+
+
 def test_select_degenerate_cases():
     L = 300
     scores = np.random.default_rng(0).random((2, L)).astype(np.float32)
