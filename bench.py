@@ -105,7 +105,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 100; 10 for --workload stack)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 25; 2 for --workload stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="long", choices=["long", "long_total", "llava7b", "stack"])
+    ap.add_argument("--workload", default="long", choices=["long", "long_total", "long_noprior", "llava7b", "stack"])
     ap.add_argument("--reuse-lse", action="store_true",
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -138,7 +138,7 @@ def main() -> int:
     if args.workload == "stack":
         return stack(args)
 
-    w = {"long": W.LONG, "long_total": W.LONG_TOTAL, "llava7b": W.LLAVA7B}[args.workload]
+    w = {"long": W.LONG, "long_total": W.LONG_TOTAL, "long_noprior": W.LONG_NOPRIOR, "llava7b": W.LLAVA7B}[args.workload]
     mode = w.modes[0]
     B, M = w.budget(), w.M
     q, k, v, mask = W.generate(w)

@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_scores_head.restype = None
         L.oracle_scores.argtypes = [fp, fp, I, I, I, dp]
         L.oracle_scores.restype = None
+        L.oracle_scores_window.argtypes = [fp, fp, I, I, I, I, dp]
+        L.oracle_scores_window.restype = None
         L.oracle_row_lse.argtypes = [fp, fp, I, I, I, dp]
         L.oracle_row_lse.restype = None
         L.oracle_protected_count.argtypes = [up, I, I]
@@ -119,6 +121,21 @@ def scores(q, k) -> np.ndarray:
     H, L, d = q.shape
     out = np.empty((H, L), dtype=np.float64)
     lib().oracle_scores(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, _p(out, ctypes.c_double))
+    return out[0] if single else out
+
+
+def scores_window(q, k, window: int) -> np.ndarray:
+    """Accumulated attention of the last ``window`` query rows only.  q, k: [H, L, d] (or [L, d]) -> float64."""
+    q, k = as_f32(q), as_f32(k)
+    single = q.ndim == 2
+    if single:
+        q, k = q[None], k[None]
+    H, L, d = q.shape
+    if not 1 <= int(window) <= L:
+        raise OracleError(-1)
+    out = np.empty((H, L), dtype=np.float64)
+    lib().oracle_scores_window(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, int(window),
+                               _p(out, ctypes.c_double))
     return out[0] if single else out
 
 

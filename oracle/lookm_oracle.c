@@ -49,13 +49,15 @@
 #define ORACLE_ERR_BUDGET_BELOW_PROTECTED (-4)
 
 /* ---- Eq. 4: accumulated attention scores of one head -------------------------------- */
-/* q, k: [L, d] float32;  scores: [L] double, A_s[j] = sum_i A_p[i, j].                  */
-void oracle_scores_head(const float *q, const float *k, int L, int d, double *scores)
+/* q, k: [L, d] float32;  scores: [L] double, A_s[j] = sum_i A_p[i, j], the sum running over the query rows
+ * i = first_row .. L-1.  Eq. 4 sums all rows (first_row = 0); an observation window of w rows - the scoring of
+ * the pooling baseline the paper compares with (Section 4.2), offered as a variant - is first_row = L - w.     */
+static void scores_from_row(const float *q, const float *k, int L, int d, int first_row, double *scores)
 {
     double *s = (double *)malloc(sizeof(double) * (size_t)(L > 0 ? L : 1));
     const double root_d = sqrt((double)d);
     for (int j = 0; j < L; ++j) scores[j] = 0.0;
-    for (int i = 0; i < L; ++i) {
+    for (int i = first_row; i < L; ++i) {
         /* row i of Q K^T / sqrt(d), causal: columns 0..i */
         double m = -INFINITY;
         for (int j = 0; j <= i; ++j) {
@@ -75,6 +77,17 @@ void oracle_scores_head(const float *q, const float *k, int L, int d, double *sc
         for (int j = 0; j <= i; ++j) scores[j] += s[j] / z;
     }
     free(s);
+}
+
+void oracle_scores_head(const float *q, const float *k, int L, int d, double *scores)
+{
+    scores_from_row(q, k, L, d, 0, scores);
+}
+
+/* scores of the last `window` query rows only (1 <= window <= L) */
+void oracle_scores_window_head(const float *q, const float *k, int L, int d, int window, double *scores)
+{
+    scores_from_row(q, k, L, d, L - window, scores);
 }
 
 /* Natural-log log-sum-exp of every row of the causal scaled logits, lse[i] = log sum_{j<=i} exp(q_i.k_j/sqrt(d)):
@@ -303,7 +316,13 @@ void oracle_scores(const float *q, const float *k, int H, int L, int d, double *
         oracle_scores_head(q + (size_t)h * L * d, k + (size_t)h * L * d, L, d, scores + (size_t)h * L);
 }
 
-/* threads the all-heads entry points will use */
+void oracle_scores_window(const float *q, const float *k, int H, int L, int d, int window, double *scores)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h)
+        oracle_scores_window_head(q + (size_t)h * L * d, k + (size_t)h * L * d, L, d, window, scores + (size_t)h * L);
+}
+
 void oracle_row_lse(const float *q, const float *k, int H, int L, int d, double *lse)
 {
 #pragma omp parallel for schedule(dynamic, 1)

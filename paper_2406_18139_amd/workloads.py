@@ -34,6 +34,7 @@ class Workload:
     modes: Tuple[str, ...]    # merge modes run on this workload
     prompt: int = 0           # prompt index (config 5 has four)
     total_budget: int = -1    # if >= 0: absolute budget B instead of the rho mapping
+    text_prior: bool = True   # False: the method is handed an all-ones mask (Table 1's rows without text prior)
 
     @property
     def n_img(self) -> int:
@@ -44,7 +45,13 @@ class Workload:
         return sum(self.spans) + self.n_img * self.img_tokens
 
     def mask(self) -> np.ndarray:
-        """uint8 [L]: 1 = image token, 0 = text token (text, image, text, ..., text)."""
+        """uint8 [L], the modality mask handed to the method: 1 = image token (evictable), 0 = text token; all ones
+        when the text prior is switched off."""
+        m = self.layout_mask()
+        return m if self.text_prior else np.ones_like(m)
+
+    def layout_mask(self) -> np.ndarray:
+        """uint8 [L]: 1 = image token, 0 = text token (text, image, text, ..., text): where the tokens really are."""
         parts = []
         for i, s in enumerate(self.spans):
             parts.append(np.zeros(s, np.uint8))
@@ -83,7 +90,7 @@ def generate(w: Workload, layer: int = 0, heads: Sequence[int] | None = None):
     from its own stream so a subset equals the matching slice of the full tensors."""
     L, d = w.L, w.d
     mask = w.mask()
-    img = mask == 1
+    img = w.layout_mask() == 1
     n_image_tok = int(img.sum())
     # one cluster id per image token, shared by heads and by K / V
     cluster = np.random.default_rng([w.seed(layer), 0xC1]).integers(0, w.C, size=n_image_tok)
@@ -113,7 +120,7 @@ def generate_on_device(w: Workload, layer: int = 0, device="cuda:0"):
     g.manual_seed(w.seed(layer))
     L, d, H = w.L, w.d, w.H
     mask = torch.from_numpy(w.mask()).to(device)
-    img = mask == 1
+    img = torch.from_numpy(w.layout_mask()).to(device) == 1
     n_image_tok = int(img.sum())
     cluster = torch.randint(0, w.C, (n_image_tok,), generator=g, device=device)
     q = torch.randn((H, L, d), generator=g, device=device)
@@ -144,6 +151,11 @@ LONG = Workload("long_20img", 4, 32, 128, "bf16", _SP4, 576, 64, 0.2, 0.10, 64, 
 # the same prompt with the paper-style total budget round(0.1 * L)
 LONG_TOTAL = Workload("long_20img_total10", 4, 32, 128, "bf16", _SP4, 576, 64, 0.2, 0.10, 64, ("pivotal",),
                       total_budget=int(np.floor(0.1 * (sum(_SP4) + 20 * 576) + 0.5)))
+
+# the same prompt without the text prior: the method sees an all-ones mask, so only the window is protected and
+# text tokens compete with image tokens by score (10 % of everything before the window survives)
+LONG_NOPRIOR = Workload("long_20img_noprior", 4, 32, 128, "bf16", _SP4, 576, 64, 0.2, 0.10, 64, ("pivotal",),
+                        text_prior=False)
 
 STACK_LAYERS = 32
 

@@ -56,6 +56,15 @@ def test_long_layer_paper_style_total_budget():
     print("long total-budget", st)
 
 
+def test_long_layer_without_text_prior():
+    # all-ones mask: only the window is protected, text competes with image tokens by score (Table 1's rows
+    # without the text prior); the oracle's kept set must then contain evicted TEXT positions' absence too
+    w = W.LONG_NOPRIOR
+    st = parity.run_and_check(w, "pivotal", heads=[0, 21], oracle_heads=[0, 1])
+    print("long, text prior off", st)
+    assert st["kept_diff_heads"] <= 1
+
+
 def test_stack_prompts_two_layers_each():
     for w in W.stack_prompts()[:2]:
         for layer in (0, 31):

@@ -39,6 +39,7 @@ MUTANTS = [
     ("literal_rule_refuses_small_budgets", "if (rule == 0 && B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;",
      "if (B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;"),
     ("ratio_truncates", "const int N = (int)floor(alpha_important * (double)L + 0.5);", "const int N = (int)floor(alpha_important * (double)L);"),
+    ("window_one_row_short", "scores_from_row(q, k, L, d, L - window, scores);", "scores_from_row(q, k, L, d, L - window + 1, scores);"),
     ("values_not_merged", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, mode, v_out", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, 0, v_out"),
 ]
 

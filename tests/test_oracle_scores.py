@@ -169,3 +169,38 @@ def test_row_lse_closed_form_for_zero_queries():
     L, d = 50, 8
     k = np.random.default_rng(3).standard_normal((L, d)).astype(np.float32)
     np.testing.assert_allclose(oracle.row_lse(np.zeros((L, d), np.float32), k), np.log(np.arange(1, L + 1)), rtol=1e-14)
+
+
+# ---- observation window: only the last w query rows are summed -------------------------------------------------
+
+@pytest.mark.parametrize("L,d,w,seed", [(40, 16, 1, 0), (40, 16, 7, 1), (96, 64, 32, 2), (130, 32, 129, 3)])
+def test_window_scores_match_library_softmax_rows(L, d, w, seed):
+    g = torch.Generator().manual_seed(900 + seed)
+    q = torch.randn(L, d, generator=g)
+    k = torch.randn(L, d, generator=g) * 1.5
+    logits = (q.double() @ k.double().T) / math.sqrt(d)
+    causal = torch.full((L, L), float("-inf"), dtype=torch.float64).triu(1)
+    ref = torch.softmax(logits + causal, dim=-1)[L - w:].sum(0).numpy()
+    got = oracle.scores_window(q, k, w)
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-300)
+    assert abs(got.sum() - w) < 1e-10                      # w rows of a softmax
+
+
+def test_window_scores_special_cases():
+    rng = np.random.default_rng(11)
+    L, d = 70, 32
+    q = rng.standard_normal((2, L, d)).astype(np.float32)
+    k = rng.standard_normal((2, L, d)).astype(np.float32)
+    np.testing.assert_array_equal(oracle.scores_window(q, k, L), oracle.scores(q, k))      # the whole prompt
+    # w = 1: the last row's attention; w rows are additive
+    last = oracle.scores_window(q[0], k[0], 1)
+    z = (q[0, -1].astype(np.float64) @ k[0].astype(np.float64).T) / math.sqrt(d)
+    np.testing.assert_allclose(last, np.exp(z - z.max()) / np.exp(z - z.max()).sum(), rtol=1e-12)
+    # zero queries: uniform rows, a closed form; columns after the window's first row see fewer rows
+    w = 9
+    got = oracle.scores_window(np.zeros((L, d), np.float32), k[0], w)
+    inv = 1.0 / np.arange(1, L + 1)
+    ref = np.array([inv[max(j, L - w):].sum() for j in range(L)])
+    np.testing.assert_allclose(got, ref, rtol=1e-13)
+    with pytest.raises(oracle.OracleError):
+        oracle.scores_window(q, k, 0)
