@@ -28,13 +28,14 @@ PEAK_MFMA_BF16 = 2.5e15   # dense bf16 MFMA, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
 
 
-def algorithmic_work(w: W.Workload) -> dict:
+def algorithmic_work(w: W.Workload, score_window: int = 0) -> dict:
     """Work the method needs per launch of each kernel (all heads of one layer); nothing a particular
     tiling adds (masked halves of diagonal tiles, padding, re-reads) is counted."""
     H, L, d, B = w.H, w.L, w.d, w.budget()
     Le = L - B
     e = 2 if w.dtype == "bf16" else 4
-    pairs = L * (L + 1) // 2
+    r0 = L - score_window if score_window > 0 else 0
+    pairs = L * (L + 1) // 2 - r0 * (r0 + 1) // 2          # causal pairs of the query rows that count
     return {
         "score_lse": ("mfma", 2.0 * d * pairs * H),
         "score_lse_fold": ("hbm", H * 4.0 * L * 3),        # two partials in, one value out (at least one chunk)
@@ -108,6 +109,8 @@ def main() -> int:
     ap.add_argument("--workload", default="long", choices=["long", "long_total", "long_noprior", "llava7b", "stack"])
     ap.add_argument("--reuse-lse", action="store_true",
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
+    ap.add_argument("--score-window", type=int, default=0,
+                    help="variant: scores from the last W query rows only (lookm_scores_window), via a lookm_job")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy kernel (to scale HBM byte counters) and exit")
     args = ap.parse_args()
@@ -157,8 +160,14 @@ def main() -> int:
             row_lse[h] = torch.logsumexp(logits.masked_fill_(causal, float("-inf")), dim=-1)
         del causal, logits
 
+    variant = args.reuse_lse or args.score_window > 0
+    job = lookm.make_job(qg, kg, vg, mg, B, M, mode, out, ws, row_lse=row_lse, score_window=args.score_window)
+
     def step():
-        lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False, row_lse=row_lse)
+        if variant:
+            lookm.lookm_compress_batch([job])
+        else:
+            lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
 
     for _ in range(args.warmup):
         step()
@@ -174,19 +183,11 @@ def main() -> int:
         print(f"bench.py: device status {status}", file=sys.stderr)
         return 1
 
-    if args.reuse_lse:
-        print(json.dumps({
-            "metric": "prompt KV tokens compressed/sec per layer (12K ctx), row log-sum-exp supplied by the prefill",
-            "value": round(w.L / (ms_per_step * 1e-3), 1), "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps,
-            "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-            "config": {"workload": f"{w.name} via lookm_compress_lse", "H": w.H, "L": w.L, "d": w.d, "budget": B,
-                       "recent_window": M, "merge_mode": mode}}))
-        return 0
-
     # per-kernel durations: HIP events recorded by the library on the launch stream, same inputs
-    kms = lookm.lookm_compress_profile(qg, kg, vg, mg, B, M, mode, max(min(args.steps, 30), 1), out, ws)
-    work = algorithmic_work(w)
+    kms = lookm.lookm_job_profile(job, max(min(args.steps, 30), 1))
+    work = algorithmic_work(w, args.score_window)
+    if args.reuse_lse:
+        kms.pop("score_lse"), kms.pop("score_lse_fold")          # not launched: the prefill's values are used
     kernels = {}
     event_gap_ms = None
     if w.dtype == "bf16" and w.d == 128:
@@ -216,18 +217,19 @@ def main() -> int:
                 "peak": dpeak / (1e12 if dbound == "mfma" else 1e9),
                 "unit": "TFLOP/s" if dbound == "mfma" else "GB/s",
                 "frac": round(dach / dpeak, 4), "traffic": traffic}
-    score_ms = kms["score_lse"] + kms["score_lse_fold"] + kms["score_colsum"] + kms["score_colsum_fold"]
+    score_ms = kms.get("score_lse", 0.0) + kms.get("score_lse_fold", 0.0) + kms["score_colsum"] + kms["score_colsum_fold"]
     smc_ms = kms["select"] + kms["bucket"] + kms["merge"]
     smc_bytes = work["select"][1] + work["bucket"][1] + work["merge"][1]
     groups = {
         "score_passes": {"ms": round(score_ms, 4), "frac_mfma_peak": round(
-            (work["score_lse"][1] + work["score_colsum"][1]) / (score_ms * 1e-3) / PEAK_MFMA_BF16, 4)},
+            ((0.0 if args.reuse_lse else work["score_lse"][1]) + work["score_colsum"][1]) / (score_ms * 1e-3)
+            / PEAK_MFMA_BF16, 4)},
         "select_bucket_merge": {"ms": round(smc_ms, 4), "GB/s": round(smc_bytes / (smc_ms * 1e-3) / 1e9, 1),
                                 "frac_hbm_peak": round(smc_bytes / (smc_ms * 1e-3) / PEAK_HBM, 4)},
     }
 
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not variant:
         import oracle
         threads = oracle.num_threads()
         n_heads = max(1, min(w.H, threads))
@@ -240,8 +242,13 @@ def main() -> int:
                         "sample": f"heads 0..{n_heads - 1} of {w.H} of the same layer (one head per thread), "
                                   f"scaled by {w.H}/{n_heads} to the whole layer"}
 
+    metric = "prompt KV tokens compressed/sec per layer (12K ctx)"
+    if args.reuse_lse:
+        metric += ", row log-sum-exp supplied by the prefill"
+    if args.score_window > 0:
+        metric += f", scores from the last {args.score_window} query rows only"
     line = {
-        "metric": "prompt KV tokens compressed/sec per layer (12K ctx)",
+        "metric": metric,
         "value": round(w.L / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -251,7 +258,8 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {w.H} heads x d{w.d} {w.dtype}, {w.n_img} images x {w.img_tokens} tokens + "
                                f"{len(w.spans)} text spans, L={w.L}, budget B={B} (k_img={w.k_img()}), "
                                f"recent_window={M}, merge={mode}",
-                   "H": w.H, "L": w.L, "d": w.d, "budget": B, "recent_window": M, "merge_mode": mode},
+                   "H": w.H, "L": w.L, "d": w.d, "budget": B, "recent_window": M, "merge_mode": mode,
+                   "row_lse_supplied": bool(args.reuse_lse), "score_window": args.score_window},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels": kernels,

@@ -195,6 +195,15 @@ int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_
  */
 int lookm_budget_from_ratios(int L, double alpha_recent, double alpha_important, int* recent_window, int* budget);
 
+/*
+ * A variant of Eq. 4: only the last `window` query rows are summed, scores_out[h, j] = sum over rows
+ * i >= L - window of the attention of row i on key j - the observation-window scoring of the pooling baseline the
+ * paper compares with (Section 4.2), on the same kernels; the work drops from L^2 to window * L.  window = L is
+ * lookm_scores.  1 <= window <= L, else LOOKM_ERR_INVALID_ARG.  Other arguments as for lookm_scores.
+ */
+int lookm_scores_window(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int window,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* lookm_select under a chosen rule (lookm_select itself is LOOKM_SELECT_PROTECT_TEXT). */
 int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L,
                        int budget, int recent_window, lookm_select_rule rule,
@@ -215,6 +224,7 @@ typedef struct lookm_job {
     int budget, recent_window;
     lookm_merge_mode merge_mode;
     lookm_select_rule rule;
+    int score_window;                /* 0: Eq. 4 as printed (all query rows); w > 0: see lookm_scores_window */
     void* k_out;
     void* v_out;
     int32_t* kept_idx;
@@ -256,6 +266,9 @@ int lookm_compress_profile(const void* q, const void* k, const void* v, const ui
                            float* scores_out, int32_t* status_out,
                            void* workspace, size_t workspace_bytes, void* hip_stream,
                            int reps, float* kernel_ms_host);
+
+/* The same for any job (selection rule, observation window, supplied row log-sum-exp). */
+int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -100,30 +100,38 @@ size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
 }
 
 static int scores_impl(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
-                       float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+                       int window, float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!q || !k || !scores_out) return LOOKM_ERR_INVALID_ARG;
     int rc = check_shape(H, L, d, (int)dt);
     if (rc != LOOKM_OK) return rc;
+    if (window < 0 || window > L) return LOOKM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(scores_out)) return LOOKM_ERR_INVALID_ARG;
     rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, 0);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, L, d, (int)dt, 0);
-    return lookm_host::launch_scores(q, k, H, L, d, dt, at<float>(workspace, w.lse), row_lse, scores_out, nullptr,
-                                     at<float>(workspace, w.partials), (hipStream_t)hip_stream);
+    return lookm_host::launch_scores(q, k, H, L, d, dt, window ? L - window : 0, at<float>(workspace, w.lse), row_lse,
+                                     scores_out, nullptr, at<float>(workspace, w.partials), (hipStream_t)hip_stream);
 }
 
 int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
                  void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    return scores_impl(q, k, nullptr, H, L, d, dt, scores_out, workspace, workspace_bytes, hip_stream);
+    return scores_impl(q, k, nullptr, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_scores_lse(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
                      float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!row_lse) return LOOKM_ERR_INVALID_ARG;
-    return scores_impl(q, k, row_lse, H, L, d, dt, scores_out, workspace, workspace_bytes, hip_stream);
+    return scores_impl(q, k, row_lse, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
+}
+
+int lookm_scores_window(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int window,
+                        float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (window <= 0) return LOOKM_ERR_INVALID_ARG;
+    return scores_impl(q, k, nullptr, H, L, d, dt, window, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L, int budget,
@@ -206,6 +214,7 @@ static int validate_job(const lookm_job& j)
     if (j.budget > 0 && (!j.k_out || !j.v_out || !j.kept_idx)) return LOOKM_ERR_INVALID_ARG;   // empty outputs may be NULL
     if ((int)j.merge_mode < LOOKM_MERGE_NONE || (int)j.merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
     if ((int)j.rule < LOOKM_SELECT_PROTECT_TEXT || (int)j.rule > LOOKM_SELECT_LITERAL) return LOOKM_ERR_INVALID_ARG;
+    if (j.score_window < 0 || j.score_window > j.L) return LOOKM_ERR_INVALID_ARG;
     int rc = check_shape(j.H, j.L, j.d, (int)j.dt);
     if (rc != LOOKM_OK) return rc;
     rc = check_budget(j.L, j.budget, j.recent_window);
@@ -231,7 +240,8 @@ static int enqueue_job(const lookm_job& j, hipStream_t st)
     // the matching needs the inverse key norms; the matrix-core score pass writes them from the key rows it holds
     const bool match = j.merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
     float* rnorm = at<float>(workspace, w.rnorm);
-    int rc = lookm_host::launch_scores(j.q, j.k, H, L, d, dt, at<float>(workspace, w.lse), j.row_lse, scores,
+    int rc = lookm_host::launch_scores(j.q, j.k, H, L, d, dt, j.score_window ? L - j.score_window : 0,
+                                       at<float>(workspace, w.lse), j.row_lse, scores,
                                        match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
     rc = lookm_host::launch_select(scores, j.modality_mask, H, L, budget, j.recent_window, (int)j.rule, j.kept_idx,
@@ -258,6 +268,7 @@ static int compress_impl(const void* q, const void* k, const void* v, const uint
     j.q = q; j.k = k; j.v = v; j.modality_mask = modality_mask; j.row_lse = row_lse;
     j.H = H; j.L = L; j.d = d; j.dt = dt;
     j.budget = budget; j.recent_window = recent_window; j.merge_mode = merge_mode; j.rule = LOOKM_SELECT_PROTECT_TEXT;
+    j.score_window = 0;
     j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
     j.workspace = workspace; j.workspace_bytes = workspace_bytes;
     const int rc = validate_job(j);
@@ -304,24 +315,21 @@ int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* 
     return LOOKM_OK;
 }
 
-int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,
-                           int d, lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode,
-                           void* k_out, void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out,
-                           void* workspace, size_t workspace_bytes, void* hip_stream, int reps, float* kernel_ms_host)
+int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, void* hip_stream)
 {
-    if (reps <= 0 || kernel_ms_host == nullptr) return LOOKM_ERR_INVALID_ARG;
+    if (!job || reps <= 0 || kernel_ms_host == nullptr) return LOOKM_ERR_INVALID_ARG;
+    int rc = validate_job(*job);
+    if (rc != LOOKM_OK) return rc;
     lookm_host::KernelTimer timer;
     timer.st = (hipStream_t)hip_stream;
     for (int i = 0; i <= LOOKM_N_KERNELS; ++i)
         if (hipEventCreate(&timer.ev[i]) != hipSuccess) return LOOKM_ERR_DEVICE;
     double sum[LOOKM_N_KERNELS] = {0};
-    int rc = LOOKM_OK;
     for (int r = 0; r < reps && rc == LOOKM_OK; ++r) {
         // a kernel that is skipped for these sizes leaves its event at the previous kernel's time
         for (int i = 0; i <= LOOKM_N_KERNELS; ++i) (void)hipEventRecord(timer.ev[i], timer.st);
         lookm_host::g_timer = &timer;
-        rc = lookm_compress(q, k, v, modality_mask, H, L, d, dt, budget, recent_window, merge_mode, k_out, v_out,
-                            kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
+        rc = enqueue_job(*job, timer.st);
         lookm_host::g_timer = nullptr;
         if (hipStreamSynchronize(timer.st) != hipSuccess) rc = LOOKM_ERR_DEVICE;
         float prev = 0.f;   // time since ev[0] of the latest kernel that actually ran
@@ -334,6 +342,21 @@ int lookm_compress_profile(const void* q, const void* k, const void* v, const ui
     for (int i = 0; i <= LOOKM_N_KERNELS; ++i) (void)hipEventDestroy(timer.ev[i]);
     for (int i = 0; i < LOOKM_N_KERNELS; ++i) kernel_ms_host[i] = (float)(sum[i] / reps);
     return rc;
+}
+
+int lookm_compress_profile(const void* q, const void* k, const void* v, const uint8_t* modality_mask, int H, int L,
+                           int d, lookm_dtype dt, int budget, int recent_window, lookm_merge_mode merge_mode,
+                           void* k_out, void* v_out, int32_t* kept_idx, float* scores_out, int32_t* status_out,
+                           void* workspace, size_t workspace_bytes, void* hip_stream, int reps, float* kernel_ms_host)
+{
+    lookm_job j;
+    j.q = q; j.k = k; j.v = v; j.modality_mask = modality_mask; j.row_lse = nullptr;
+    j.H = H; j.L = L; j.d = d; j.dt = dt;
+    j.budget = budget; j.recent_window = recent_window; j.merge_mode = merge_mode; j.rule = LOOKM_SELECT_PROTECT_TEXT;
+    j.score_window = 0;
+    j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
+    j.workspace = workspace; j.workspace_bytes = workspace_bytes;
+    return lookm_job_profile(&j, reps, kernel_ms_host, hip_stream);
 }
 
 }  // extern "C"

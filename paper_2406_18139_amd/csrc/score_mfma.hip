@@ -79,11 +79,18 @@ __device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb,
 // for every strip, and work is enumerated chunk-major, so the workgroups resident on an XCD at one
 // time stream the SAME rows of the same head and share them in that XCD's L2.  Each workgroup writes a
 // partial result per stationary row; a small second kernel folds a strip's chunks together in order.
-__host__ __device__ inline int first_chunk(int pass, int t, int CT) { return (pass == 1) ? 0 : (t * BS) / CT; }
-__host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT)
+//
+// With an observation window only the query rows R0 .. L-1 count (R0 = 0: all rows, Eq. 4 as printed): pass 1
+// then needs only the strips that hold such rows, and pass 2 streams a strip's query rows from max(strip start,
+// R0) on, so the chunks below R0 are empty for every strip.
+__host__ __device__ inline int first_chunk(int pass, int t, int CT, int R0)
 {
-    if (pass == 1) return (min(L, (t + 1) * BS) + CT - 1) / CT;
-    return (L + CT - 1) / CT - (t * BS) / CT;
+    return (pass == 1) ? 0 : max(t * BS, R0) / CT;
+}
+__host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT, int R0)
+{
+    if (pass == 1) return ((t + 1) * BS > R0) ? (min(L, (t + 1) * BS) + CT - 1) / CT : 0;
+    return (L + CT - 1) / CT - max(t * BS, R0) / CT;
 }
 
 // The matrix pipe and the vector ALU of a SIMD overlap ACROSS waves, not within one (measured: an MFMA
@@ -95,9 +102,9 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT)
 //   zero key) for the matching of Eq. 9, from the registers it holds anyway - the keys are not read again for it.
 template <int PASS>
 __global__ void __launch_bounds__(256, 3)
-k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, float scale2, int C, int U,
-             const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a, float* __restrict__ part_b,
-             float* __restrict__ rnorm)
+k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, int R0, float scale2, int C,
+             int U, const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a,
+             float* __restrict__ part_b, float* __restrict__ rnorm)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
@@ -117,9 +124,9 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     }
     if (h >= H || e >= U) return;
     const int nS = (L + BS - 1) / BS, CT = C * BX;
-    int g = 0, tile = 0;
+    int g = (PASS == 1) ? 0 : R0 / CT, tile = 0;
     for (;; ++g) {      // chunk-major enumeration: all strips that touch chunk g, then chunk g+1, ...
-        const int t_first = (PASS == 1) ? (g * CT) / BS : 0;
+        const int t_first = (PASS == 1) ? max((g * CT) / BS, R0 / BS) : 0;
         const int cnt = (PASS == 1) ? nS - t_first : min(nS, ((g + 1) * CT + BS - 1) / BS);
         if (e < cnt) { tile = t_first + e; break; }
         e -= cnt;
@@ -149,7 +156,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     const int strip_begin = (PASS == 1) ? 0 : s0;
     const int strip_end = (PASS == 1) ? min(L, s0 + BS) : L;
-    const int x_begin = max(strip_begin, g * CT);
+    const int x_begin = max(max(strip_begin, g * CT), (PASS == 2) ? (R0 / BX) * BX : 0);   // tile-aligned
     const int x_end = min(strip_end, (g + 1) * CT);
     const int n_it = (x_end - x_begin + BX - 1) / BX;
 
@@ -170,7 +177,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                                              (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW],
                                              16, 0, 0);
         }
-        if (PASS == 2 && tid < BX) stage_l = (x0 + tid < L) ? lse_h[x0 + tid] : INFINITY;   // negated at store time
+        if (PASS == 2 && tid < BX)   // negated at store time; rows outside [R0, L) get +inf and contribute nothing
+            stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
     };
     auto store_tile = [&](int buf) {
         if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
@@ -182,7 +190,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     load_tile(x_begin, 0);
     store_tile(0);
-    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT)) {
+    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0)) {
         // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
         // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
         // partial sums, number p over groups p and p + 8, then a pairwise tree), so both give the same bits
@@ -295,14 +303,15 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 // pass 2 -> scores[h, j] = A_s[j].  One thread per (head, row).
 template <int PASS>
 __global__ void __launch_bounds__(256)
-k_score_combine(int H, int L, int C, int U, const float* __restrict__ part_a, const float* __restrict__ part_b,
+k_score_combine(int H, int L, int R0, int C, const float* __restrict__ part_a, const float* __restrict__ part_b,
                 float* __restrict__ out)
 {
     const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
     const int row = tile * BS + r;
     if (row >= L) return;
     const int CT = C * BX, nS = gridDim.x, G = (L + CT - 1) / CT;
-    const int g0 = first_chunk(PASS, tile, CT), nc = strip_chunks(PASS, tile, L, CT);
+    const int g0 = first_chunk(PASS, tile, CT, R0), nc = strip_chunks(PASS, tile, L, CT, R0);
+    if (nc == 0) return;     // pass 1 under a window: a strip with no row that counts (its values are never read)
     const size_t stride = (size_t)nS * BS;      // from one chunk of a strip to the next
     const float* pa = part_a + (((size_t)h * G + g0) * nS + tile) * BS + r;
     const float* pb = part_b + (((size_t)h * G + g0) * nS + tile) * BS + r;
@@ -336,11 +345,11 @@ static int chunk_tiles(int H, int L)
     return (int)(c < 8 ? 8 : (c > 256 ? 256 : c));
 }
 
-static int total_chunks(int pass, int L, int C)
+static int total_chunks(int pass, int L, int C, int R0)
 {
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     int u = 0;
-    for (int t = 0; t < nS; ++t) u += lookm::strip_chunks(pass, t, L, C * lookm::BX);
+    for (int t = 0; t < nS; ++t) u += lookm::strip_chunks(pass, t, L, C * lookm::BX, R0);
     return u;
 }
 
@@ -360,13 +369,14 @@ size_t scores_mfma_scratch_floats(int H, int L)
     return (size_t)2 * H * G * nS * lookm::BS;
 }
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float* lse, const float* lse_in,
+int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, int R0, float* lse, const float* lse_in,
                        float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     const int C = chunk_tiles(H, L);
-    const int U1 = total_chunks(1, L, C), U2 = total_chunks(2, L, C);
+    // the chunk length is the full problem's also under a window, so the partial arrays keep their layout and size
+    const int U1 = total_chunks(1, L, C, R0), U2 = total_chunks(2, L, C, R0);
     const int G = (L + C * lookm::BX - 1) / (C * lookm::BX);
     float* part_a = scratch;
     float* part_b = scratch + (size_t)H * G * nS * lookm::BS;
@@ -374,17 +384,17 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, float*
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
     if (!lse_in) {
-        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, scale2, C,
-                           U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
+        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, R0, scale2,
+                           C, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
         mark(LOOKM_K_SCORE_LSE);
-        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, C, U1, part_a, part_b, lse);
+        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, R0, C, part_a, part_b, lse);
         mark(LOOKM_K_SCORE_LSE_FOLD);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
-    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, scale2, C, U2,
-                       lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
+    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, R0, scale2, C,
+                       U2, lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
     mark(LOOKM_K_SCORE_COLSUM);
-    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, C, U2, part_a, part_b, scores);
+    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, R0, C, part_a, part_b, scores);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);
     return hip_ok(hipGetLastError());
 }

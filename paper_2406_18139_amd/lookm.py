@@ -32,7 +32,7 @@ SELECT_RULES = {"protect_text": 0, "literal": 1}
 EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
-           "lookm_select_rule_", "lookm_compress_batch"]
+           "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -44,7 +44,7 @@ class Job(ctypes.Structure):
                 ("modality_mask", ctypes.c_void_p), ("row_lse", ctypes.c_void_p),
                 ("H", ctypes.c_int), ("L", ctypes.c_int), ("d", ctypes.c_int), ("dt", ctypes.c_int),
                 ("budget", ctypes.c_int), ("recent_window", ctypes.c_int), ("merge_mode", ctypes.c_int),
-                ("rule", ctypes.c_int),
+                ("rule", ctypes.c_int), ("score_window", ctypes.c_int),
                 ("k_out", ctypes.c_void_p), ("v_out", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
                 ("scores_out", ctypes.c_void_p), ("status_out", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
@@ -96,6 +96,10 @@ def lib() -> ctypes.CDLL:
         L.lookm_budget_from_ratios.argtypes = [I, ctypes.c_double, ctypes.c_double, ctypes.POINTER(I), ctypes.POINTER(I)]
         L.lookm_select_rule_.restype = I
         L.lookm_select_rule_.argtypes = [vp, vp, I, I, I, I, I, vp, vp, vp, vp]
+        L.lookm_scores_window.restype = I
+        L.lookm_scores_window.argtypes = [vp, vp, I, I, I, I, I, vp, vp, sz, vp]
+        L.lookm_job_profile.restype = I
+        L.lookm_job_profile.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(ctypes.c_float), vp]
         L.lookm_compress_batch.restype = I
         L.lookm_compress_batch.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(I), vp]
         _lib = L
@@ -186,19 +190,20 @@ class Compressed:
 def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode,
                    want_scores: bool = False, out: Optional[Compressed] = None,
                    workspace: Optional[torch.Tensor] = None, check: bool = True,
-                   row_lse: Optional[torch.Tensor] = None, rule="protect_text") -> Compressed:
+                   row_lse: Optional[torch.Tensor] = None, rule="protect_text", score_window: int = 0) -> Compressed:
     """One layer's compression.  q, k, v: GPU tensors [H, L, d]; modality_mask: GPU uint8 [L].
     ``check=True`` synchronises to read the device status word and raises on failure.
     With ``row_lse`` (GPU float32 [H, L]) the call forwards to lookm_compress_lse; with a selection rule other
-    than the default it forwards to lookm_compress_batch as a single job (the entry point that takes a rule)."""
-    if _rule(rule) != 0:
+    than the default, or an observation window for the scores, it forwards to lookm_compress_batch as a single job
+    (the entry point that takes them)."""
+    if _rule(rule) != 0 or int(score_window) != 0:
         H, L, d = q.shape
         if out is None:
             out = alloc_outputs(H, L, d, int(budget), q.dtype, q.device, want_scores)
         if workspace is None:
             workspace = alloc_workspace(H, L, d, min(max(int(budget), 0), L), _dt(q), q.device)
         lookm_compress_batch([make_job(q, k, v, modality_mask, budget, recent_window, merge_mode, out, workspace,
-                                       row_lse=row_lse, rule=rule)])
+                                       row_lse=row_lse, rule=rule, score_window=score_window)])
         if check:
             st = int(out.status.item())
             if st != OK:
@@ -234,7 +239,8 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
 
 
 def make_job(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode, out: Compressed,
-             workspace: torch.Tensor, row_lse: Optional[torch.Tensor] = None, rule="protect_text") -> Job:
+             workspace: torch.Tensor, row_lse: Optional[torch.Tensor] = None, rule="protect_text",
+             score_window: int = 0) -> Job:
     """A struct lookm_job over the given tensors (which the caller keeps alive until the work has run)."""
     H, L, d = q.shape
     if row_lse is not None and (row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (H, L)):
@@ -242,7 +248,8 @@ def make_job(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode
     wp, wn = _ws_ptr(workspace)
     return Job(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
                _dev(row_lse, "row_lse") if row_lse is not None else None, H, L, d, _dt(q), int(budget),
-               int(recent_window), _mode(merge_mode), _rule(rule), _dev(out.k_out, "k_out"), _dev(out.v_out, "v_out"),
+               int(recent_window), _mode(merge_mode), _rule(rule), int(score_window), _dev(out.k_out, "k_out"),
+               _dev(out.v_out, "v_out"),
                _dev(out.kept_idx, "kept_idx"), _dev(out.scores, "scores") if out.scores is not None else None,
                _dev(out.status, "status"), wp, wn)
 
@@ -284,6 +291,15 @@ def lookm_compress_profile(q, k, v, modality_mask, budget: int, recent_window: i
     return {name: float(ms[i]) for i, name in enumerate(KERNELS)}
 
 
+def lookm_job_profile(job: Job, reps: int) -> dict:
+    """lookm_job_profile: the job run ``reps`` times with an event after every kernel -> {kernel: average ms}."""
+    ms = (ctypes.c_float * len(KERNELS))()
+    rc = lib().lookm_job_profile(ctypes.byref(job), int(reps), ms, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_job_profile")
+    return {name: float(ms[i]) for i, name in enumerate(KERNELS)}
+
+
 def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
     H, L, d = q.shape
     dt = _dt(q)
@@ -294,6 +310,20 @@ def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor
     rc = lib().lookm_scores(_dev(q, "q"), _dev(k, "k"), H, L, d, dt, scores.data_ptr(), wp, wn, _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_scores")
+    return scores
+
+
+def lookm_scores_window(q, k, window: int, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    H, L, d = q.shape
+    dt = _dt(q)
+    scores = torch.empty((H, L), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, 0, dt, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_scores_window(_dev(q, "q"), _dev(k, "k"), H, L, d, dt, int(window), scores.data_ptr(), wp, wn,
+                                   _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_scores_window")
     return scores
 
 

@@ -202,3 +202,27 @@ def test_batch_call_equals_single_calls():
     with pytest.raises(lookm.LookmError) as e:
         lookm.lookm_compress_batch([jobs[0], bad])
     assert e.value.code == lookm.ERR_BUDGET_RANGE and "job 1" in str(e.value)
+
+
+def test_compress_with_an_observation_window():
+    # scores from the last 64 query rows only; everything downstream unchanged
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w, heads=[4, 7])
+    qg, kg, vg, mg = q.cuda(), k.cuda(), v.cuda(), mask.cuda()
+    B, M, win = w.budget(), w.M, 64
+    res = lookm.lookm_compress(qg, kg, vg, mg, B, M, "pivotal", want_scores=True, score_window=win)
+    ref_scores = oracle.scores_window(q, k, win)
+    sg = res.scores.cpu().numpy().astype(np.float64)
+    np.testing.assert_allclose(sg, ref_scores, rtol=2e-5, atol=1e-12)
+    kept = res.kept_idx.cpu().numpy()
+    mask_np = mask.numpy()
+    for h in range(2):
+        # both sides deciding on the kernel's own scores
+        assert kept[h].tolist() == oracle.select(sg[h], mask_np, B, M)[0].tolist()
+    parity.check_kept(kept, sg, ref_scores, np.stack([oracle.select(ref_scores[h], mask_np, B, M)[0] for h in range(2)]),
+                      mask_np, B, M)
+    ev = torch.from_numpy(np.stack([np.setdiff1d(np.arange(w.L, dtype=np.int32), kept[h]) for h in range(2)])).cuda()
+    a, s = lookm.lookm_nearest(kg, res.kept_idx, ev)
+    for h in range(2):
+        parity.check_merge(k[h].float().numpy(), kept[h], ev[h].cpu().numpy(), a[h].cpu().numpy(), s[h].cpu().numpy(),
+                           "pivotal", res.k_out[h].float().cpu().numpy(), torch.bfloat16)

@@ -75,6 +75,26 @@ def test_scores_from_a_supplied_row_lse(H, L, d, dtype):
     assert (np.abs(own - s) / ref).max() < 1e-5       # both routes agree
 
 
+@pytest.mark.parametrize("H,L,d,dtype,windows", [
+    (2, 700, 128, torch.bfloat16, (1, 63, 64, 65, 300, 699, 700)),      # matrix cores: inside one tile, across chunks
+    (2, 3000, 128, torch.bfloat16, (17, 256, 1000, 2999)),
+    (1, 333, 64, torch.bfloat16, (5, 200)),                             # portable kernels
+    (2, 256, 64, torch.float32, (16, 255)),
+])
+def test_window_scores_match_oracle(H, L, d, dtype, windows):
+    q, k = rand_qk(H, L, d, dtype, seed=L + d)
+    qg, kg = q.cuda(), k.cuda()
+    for w in windows:
+        s = lookm.lookm_scores_window(qg, kg, w).cpu().numpy().astype(np.float64)
+        ref = oracle.scores_window(q, k, w)
+        assert np.all(np.isfinite(s))
+        # columns that only far-away rows look at can be tiny: relative where it matters, absolute below
+        np.testing.assert_allclose(s, ref, rtol=2e-5, atol=1e-12)
+        np.testing.assert_allclose(s.sum(1), w, rtol=2e-5)
+    full = lookm.lookm_scores(qg, kg)
+    assert torch.equal(lookm.lookm_scores_window(qg, kg, L), full)       # the whole prompt: the same launches
+
+
 def select_case(scores, mask, B, M):
     sg = torch.from_numpy(np.asarray(scores, np.float32)).cuda()
     mg = torch.from_numpy(np.asarray(mask, np.uint8)).cuda()
