@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_scores.restype = None
         L.oracle_scores_window.argtypes = [fp, fp, I, I, I, I, dp]
         L.oracle_scores_window.restype = None
+        L.oracle_decode.argtypes = [fp, fp, fp, I, I, I, I, dp]
+        L.oracle_decode.restype = None
         L.oracle_row_lse.argtypes = [fp, fp, I, I, I, dp]
         L.oracle_row_lse.restype = None
         L.oracle_protected_count.argtypes = [up, I, I]
@@ -137,6 +139,20 @@ def scores_window(q, k, window: int) -> np.ndarray:
     lib().oracle_scores_window(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, int(window),
                                _p(out, ctypes.c_double))
     return out[0] if single else out
+
+
+def decode(q, k, v, S: int | None = None) -> np.ndarray:
+    """Eq. 3: Softmax(q K^T / sqrt(d)) V for one new token per head.  q: [H, d]; k, v: [H, rows, d]; the first S rows
+    (default all) are attended.  -> float64 [H, d]."""
+    q, k, v = as_f32(q), as_f32(k), as_f32(v)
+    H, rows, d = k.shape
+    S = rows if S is None else int(S)
+    if not (1 <= S <= rows) or q.shape != (H, d) or v.shape != k.shape:
+        raise OracleError(-1)
+    out = np.empty((H, d), dtype=np.float64)
+    f = ctypes.c_float
+    lib().oracle_decode(_p(q, f), _p(k, f), _p(v, f), H, rows, S, d, _p(out, ctypes.c_double))
+    return out
 
 
 def row_lse(q, k) -> np.ndarray:

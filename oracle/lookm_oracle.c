@@ -330,6 +330,40 @@ void oracle_row_lse(const float *q, const float *k, int H, int L, int d, double 
         oracle_row_lse_head(q + (size_t)h * L * d, k + (size_t)h * L * d, L, d, lse + (size_t)h * L);
 }
 
+/* ---- Eq. 3: attention of one new token over a (compressed or full) cache ------------------------------ */
+/* q: [d]; k, v: [S, d] float32 (the first S rows of the cache, the new token's own key and value included by the
+ * caller, Eq. 2); out: [d] double = Softmax(q K^T / sqrt(d)) V.                                              */
+void oracle_decode_head(const float *q, const float *k, const float *v, int S, int d, double *out)
+{
+    double *p = (double *)malloc(sizeof(double) * (size_t)(S > 0 ? S : 1));
+    const double root_dim = sqrt((double)d);
+    double peak = -INFINITY;
+    for (int r = 0; r < S; ++r) {
+        double dot = 0.0;
+        for (int c = 0; c < d; ++c) dot += (double)q[c] * (double)k[(size_t)r * d + c];
+        p[r] = dot / root_dim;
+        if (p[r] > peak) peak = p[r];
+    }
+    double total = 0.0;
+    for (int r = 0; r < S; ++r) {
+        p[r] = exp(p[r] - peak);
+        total += p[r];
+    }
+    for (int c = 0; c < d; ++c) out[c] = 0.0;
+    for (int r = 0; r < S; ++r)
+        for (int c = 0; c < d; ++c) out[c] += (p[r] / total) * (double)v[(size_t)r * d + c];
+    free(p);
+}
+
+/* q: [H, d]; k, v: [H, rows, d] of which the first S rows are attended; out: [H, d] */
+void oracle_decode(const float *q, const float *k, const float *v, int H, int rows, int S, int d, double *out)
+{
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int h = 0; h < H; ++h)
+        oracle_decode_head(q + (size_t)h * d, k + (size_t)h * rows * d, v + (size_t)h * rows * d, S, d,
+                           out + (size_t)h * d);
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP

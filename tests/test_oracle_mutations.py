@@ -12,7 +12,7 @@ ROOT = Path(__file__).resolve().parent.parent
 SRC = (ROOT / "oracle" / "lookm_oracle.c").read_text()
 
 PIN_FILES = ["tests/test_oracle_scores.py", "tests/test_oracle_select.py", "tests/test_oracle_nearest.py",
-             "tests/test_oracle_merge.py", "tests/test_oracle_end_to_end.py"]
+             "tests/test_oracle_merge.py", "tests/test_oracle_end_to_end.py", "tests/test_oracle_decode.py"]
 
 # (name, text to find, replacement) - each must occur exactly once in the source
 MUTANTS = [
@@ -40,6 +40,8 @@ MUTANTS = [
      "if (B < oracle_protected_count(mask, L, M)) return ORACLE_ERR_BUDGET_BELOW_PROTECTED;"),
     ("ratio_truncates", "const int N = (int)floor(alpha_important * (double)L + 0.5);", "const int N = (int)floor(alpha_important * (double)L);"),
     ("window_one_row_short", "scores_from_row(q, k, L, d, L - window, scores);", "scores_from_row(q, k, L, d, L - window + 1, scores);"),
+    ("decode_without_scale", "p[r] = dot / root_dim;", "p[r] = dot;"),
+    ("decode_unnormalised", "out[c] += (p[r] / total) * (double)v[(size_t)r * d + c];", "out[c] += p[r] * (double)v[(size_t)r * d + c];"),
     ("values_not_merged", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, mode, v_out", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, 0, v_out"),
 ]
 
