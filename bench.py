@@ -100,13 +100,57 @@ def stack(args) -> int:
     return 0
 
 
+def decode(args) -> int:
+    """The step after the path (Eq. 3): one new token per head attends to the cache of the headline prompt, once
+    uncompressed (L rows) and once compressed (B rows).  A step is one lookm_decode_attention call over all 32 heads
+    of one layer; the figure Table 4 of the paper is about is the ratio of the two."""
+    dev = torch.device("cuda:0")
+    w = W.LONG
+    B = w.budget()
+    g = torch.Generator(device=dev)
+    g.manual_seed(w.seed())
+    dt = w.torch_dtype()
+    q = torch.randn((w.H, w.d), generator=g, device=dev).to(dt)
+    k = torch.randn((w.H, w.L, w.d), generator=g, device=dev).to(dt)
+    v = torch.randn((w.H, w.L, w.d), generator=g, device=dev).to(dt)
+    kc, vc = k[:, :B].contiguous(), v[:, :B].contiguous()        # same bytes per row as a compressed cache
+    out = torch.empty((w.H, w.d), dtype=dt, device=dev)
+    ws = torch.empty(int(lookm.lib().lookm_decode_workspace_bytes(w.H, w.d)) + 256, dtype=torch.uint8, device=dev)
+    res = {}
+    for name, kk, vv in (("full", k, v), ("compressed", kc, vc)):
+        for _ in range(args.warmup):
+            lookm.lookm_decode_attention(q, kk, vv, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            lookm.lookm_decode_attention(q, kk, vv, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / args.steps * 1e3
+        S = kk.shape[1]
+        nbytes = 2.0 * w.H * S * w.d * 2 + 2.0 * w.H * w.d * 2
+        res[name] = {"rows": S, "ms": round(ms, 5), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                     "frac_hbm_peak": round(nbytes / (ms * 1e-3) / PEAK_HBM, 4)}
+    c = res["compressed"]
+    print(json.dumps({
+        "metric": "decode-step attention over the compressed cache of the 12K-token prompt (one layer, 32 heads)",
+        "value": round(c["ms"] * 1e3, 2), "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": c["ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": w.dtype,
+        "data": "synthetic (drawn on the GPU)",
+        "config": {"workload": f"decode: {w.H} heads x d{w.d} {w.dtype}, cache of {B} rows (compressed) vs {w.L} rows (full)"},
+        "roofline": {"kernel": "decode (partial + merge launches)", "bound": "hbm", "achieved": c["GB/s"], "peak": 8000.0,
+                     "unit": "GB/s", "frac": c["frac_hbm_peak"], "traffic": None},
+        "full_cache": res["full"], "compressed_cache": c,
+        "speedup_over_full_cache": round(res["full"]["ms"] / c["ms"], 2)}))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed steps (default 100; 10 for --workload stack)")
     ap.add_argument("--warmup", type=int, default=None, help="untimed steps (default 25; 2 for --workload stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", default="long", choices=["long", "long_total", "long_noprior", "llava7b", "stack"])
+    ap.add_argument("--workload", default="long", choices=["long", "long_total", "long_noprior", "llava7b", "stack", "decode"])
     ap.add_argument("--reuse-lse", action="store_true",
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
     ap.add_argument("--score-window", type=int, default=0,
@@ -140,6 +184,8 @@ def main() -> int:
 
     if args.workload == "stack":
         return stack(args)
+    if args.workload == "decode":
+        return decode(args)
 
     w = {"long": W.LONG, "long_total": W.LONG_TOTAL, "long_noprior": W.LONG_NOPRIOR, "llava7b": W.LLAVA7B}[args.workload]
     mode = w.modes[0]

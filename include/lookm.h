@@ -242,6 +242,23 @@ typedef struct lookm_job {
  */
 int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream);
 
+/* ---- the step after the path: one new token attends to the (compressed) cache ------------------------------ */
+
+/* Bytes of device scratch lookm_decode_attention needs; 0 on invalid sizes.  256-byte aligned. */
+size_t lookm_decode_workspace_bytes(int H, int d);
+
+/*
+ * Section 3.1, Eq. 3: out[h] = Softmax(q[h] . K[h]^T / sqrt(d)) V[h] over the first S rows of each head's cache -
+ * what every decoding step does with the conserved cache (K_c, V_c) of Eq. 6-7, after the new token's own key
+ * and value have been appended (Eq. 2; the caller does that).  The order of the cache rows does not matter.
+ *   q        device, [H, d] of dtype dt.
+ *   k_cache, v_cache  device, [H, rows, d] of dtype dt (head stride rows * d); rows 0 .. S-1 are attended.
+ *   out      device, [H, d] of dtype dt (fp32 accumulation, one rounding).
+ *   1 <= S <= rows, else LOOKM_ERR_INVALID_ARG; d as for lookm_compress.
+ */
+int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cache, int H, int rows, int S, int d,
+                           lookm_dtype dt, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* ---- measurement aid ------------------------------------------------------------------------------- */
 
 /* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;

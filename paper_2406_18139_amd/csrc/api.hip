@@ -315,6 +315,28 @@ int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* 
     return LOOKM_OK;
 }
 
+size_t lookm_decode_workspace_bytes(int H, int d)
+{
+    if (H <= 0 || d <= 0 || d % 8 != 0 || d > 256) return 0;
+    return lookm_host::decode_scratch_bytes(H, d);
+}
+
+int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cache, int H, int rows, int S, int d,
+                           lookm_dtype dt, void* out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    if (!q || !k_cache || !v_cache || !out) return LOOKM_ERR_INVALID_ARG;
+    if (H <= 0 || rows <= 0 || S <= 0 || S > rows || d <= 0) return LOOKM_ERR_INVALID_ARG;
+    if (dt != LOOKM_F32 && dt != LOOKM_BF16) return LOOKM_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 256) return LOOKM_ERR_UNSUPPORTED;
+    if ((double)H * (double)rows * (double)d >= 1099511627776.0) return LOOKM_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return LOOKM_ERR_INVALID_ARG;
+    if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+        workspace_bytes < lookm_host::decode_scratch_bytes(H, d))
+        return LOOKM_ERR_WORKSPACE;
+    return lookm_host::launch_decode(q, k_cache, v_cache, H, rows, S, d, dt, out, static_cast<float*>(workspace),
+                                     (hipStream_t)hip_stream);
+}
+
 int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, void* hip_stream)
 {
     if (!job || reps <= 0 || kernel_ms_host == nullptr) return LOOKM_ERR_INVALID_ARG;

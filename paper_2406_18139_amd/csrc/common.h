@@ -92,6 +92,10 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
                  const float* sim, int H, int L, int d, lookm_dtype dt, int budget, int mode, int32_t* plan_words,
                  int32_t* member_pos, float* member_w, void* k_out, void* v_out, hipStream_t st);
 
+int launch_decode(const void* q, const void* k, const void* v, int H, int rows, int S, int d, lookm_dtype dt, void* out,
+                  float* part, hipStream_t st);
+size_t decode_scratch_bytes(int H, int d);
+
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }
 
 // Per-kernel timing for lookm_compress_profile: when a timer is installed, every launcher records an

@@ -32,7 +32,8 @@ SELECT_RULES = {"protect_text": 0, "literal": 1}
 EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "lookm_workspace_bytes",
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
-           "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile"]
+           "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile", "lookm_decode_workspace_bytes",
+           "lookm_decode_attention"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -98,6 +99,10 @@ def lib() -> ctypes.CDLL:
         L.lookm_select_rule_.argtypes = [vp, vp, I, I, I, I, I, vp, vp, vp, vp]
         L.lookm_scores_window.restype = I
         L.lookm_scores_window.argtypes = [vp, vp, I, I, I, I, I, vp, vp, sz, vp]
+        L.lookm_decode_workspace_bytes.restype = sz
+        L.lookm_decode_workspace_bytes.argtypes = [I, I]
+        L.lookm_decode_attention.restype = I
+        L.lookm_decode_attention.argtypes = [vp, vp, vp, I, I, I, I, I, vp, vp, sz, vp]
         L.lookm_job_profile.restype = I
         L.lookm_job_profile.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(ctypes.c_float), vp]
         L.lookm_compress_batch.restype = I
@@ -289,6 +294,25 @@ def lookm_compress_profile(q, k, v, modality_mask, budget: int, recent_window: i
     if rc != OK:
         raise LookmError(rc, "lookm_compress_profile")
     return {name: float(ms[i]) for i, name in enumerate(KERNELS)}
+
+
+def lookm_decode_attention(q, k_cache, v_cache, S: Optional[int] = None, out: Optional[torch.Tensor] = None,
+                           workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 3 for one new token per head.  q: GPU [H, d]; k_cache, v_cache: GPU [H, rows, d]; the first S rows
+    (default all) are attended.  Returns [H, d] in the inputs' dtype."""
+    H, rows, d = k_cache.shape
+    S = rows if S is None else int(S)
+    dt = _dt(q)
+    if out is None:
+        out = torch.empty((H, d), dtype=q.dtype, device=q.device)
+    if workspace is None:
+        workspace = torch.empty(int(lib().lookm_decode_workspace_bytes(H, d)) + 256, dtype=torch.uint8, device=q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_decode_attention(_dev(q, "q"), _dev(k_cache, "k_cache"), _dev(v_cache, "v_cache"), H, rows, S, d,
+                                      dt, _dev(out, "out"), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_decode_attention")
+    return out
 
 
 def lookm_job_profile(job: Job, reps: int) -> dict:

@@ -145,6 +145,23 @@ def test_budget_from_ratios_matches_the_oracle():
     assert L.lookm_select_rule_(FAKE, FAKE, 1, 8, 4, 0, 3, FAKE, FAKE, FAKE, None) == lookm.ERR_INVALID_ARG
 
 
+def test_decode_rejects_bad_arguments():
+    L = lookm.lib()
+    ok = L.lookm_decode_workspace_bytes(32, 128)
+    assert ok > 0 and L.lookm_decode_workspace_bytes(32, 100) == 0 and L.lookm_decode_workspace_bytes(0, 128) == 0
+    def call(**kw):
+        a = dict(q=FAKE, k=FAKE, v=FAKE, H=2, rows=64, S=64, d=64, dt=0, out=FAKE, ws=FAKE, wsn=1 << 24, st=None)
+        a.update(kw)
+        return L.lookm_decode_attention(*[a[n] for n in ("q", "k", "v", "H", "rows", "S", "d", "dt", "out", "ws", "wsn", "st")])
+
+    assert call(q=None) == lookm.ERR_INVALID_ARG
+    assert call(S=0) == lookm.ERR_INVALID_ARG and call(S=65) == lookm.ERR_INVALID_ARG
+    assert call(d=20) == lookm.ERR_UNSUPPORTED
+    assert call(dt=3) == lookm.ERR_INVALID_ARG
+    assert call(out=FAKE + 8) == lookm.ERR_INVALID_ARG
+    assert call(wsn=16) == lookm.ERR_WORKSPACE and call(ws=None) == lookm.ERR_WORKSPACE
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 8, 8)
