@@ -26,7 +26,7 @@ namespace lookm {
 typedef __attribute__((ext_vector_type(8))) __bf16 nbf16x8;
 typedef __attribute__((ext_vector_type(16))) float nf32x16;
 
-constexpr int ND = 128, NBS = 256, NBX = 64, NXSTRIDE = 136;
+constexpr int ND = 128, NBS = 256, NBX = 64, NXROW = 128;   // LDS rows are unpadded, chunks swizzled
 
 // partial result of one (evicted strip, chunk): key = float bits of t >> 4, slot
 struct NearestPartial {
@@ -39,7 +39,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                const int32_t* __restrict__ evicted, int H, int L, int B, int Le, int n_strips, int n_chunks, int CT,
                NearestPartial* __restrict__ part)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xs[2][NBX * NXSTRIDE];
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][NBX * NXROW];
     __shared__ __attribute__((aligned(16))) float xr[2][NBX];
 
     // XCD-affine enumeration (see k_score_mfma): units of a head are chunk-major
@@ -83,11 +83,13 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     const int x_begin = chunk * CT, x_end = min(B, x_begin + CT);
     const int n_it = (x_end - x_begin + NBX - 1) / NBX;
     const int ld_row = tid >> 4, ld_chunk = tid & 15;
-    // Staging registers are plain scalars (an array captured by the helpers ended up in scratch memory).
-    // Slots past the end of the conserved list are staged as copies of the last conserved key: they tie
-    // with it and lose on the slot rule.  The gather is two dependent loads (position, then row); the
-    // positions are fetched one tile ahead of the rows so that neither wait is exposed.
-    uint4 st0, st1, st2, st3;
+    // Conserved rows go from global memory straight into LDS (global_load_lds_dwordx4, as in the score passes): the
+    // 64 lanes of a wave fill 1 KB = 4 consecutive LDS rows, lane l landing at chunk l%16 of row l/16, and fetch
+    // chunk (l%16) ^ (row & 7) of their row, so that the fragment reads below are conflict-free without padding.
+    // The gather is two dependent loads (position, then row); the positions are fetched one tile ahead of the rows
+    // so that neither wait is exposed.  Slots past the end of the conserved list are staged as copies of the last
+    // conserved key: they tie with it and lose on the slot rule.  (Index registers are plain scalars: an array
+    // captured by a helper ended up in scratch memory.)
     float stage_r = 0.f;
     int ix0, ix1, ix2, ix3, ridx = 0;
 #define LOOKM_LOAD_INDEX(x0)                                   \
@@ -98,21 +100,21 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         ix3 = kept[min((x0) + ld_row + 48, B - 1)];            \
         if (tid < NBX) ridx = kept[min((x0) + tid, B - 1)];    \
     } while (0)
-#define LOOKM_LOAD_TILE()                                                                      \
-    do {                                                                                       \
-        st0 = *reinterpret_cast<const uint4*>(k + (size_t)ix0 * ND + ld_chunk * 8);            \
-        st1 = *reinterpret_cast<const uint4*>(k + (size_t)ix1 * ND + ld_chunk * 8);            \
-        st2 = *reinterpret_cast<const uint4*>(k + (size_t)ix2 * ND + ld_chunk * 8);            \
-        st3 = *reinterpret_cast<const uint4*>(k + (size_t)ix3 * ND + ld_chunk * 8);            \
-        if (tid < NBX) stage_r = rnorm[ridx];                                                  \
+#define LOOKM_ROW_TO_LDS(ix, j, buf)                                                                              \
+    __builtin_amdgcn_global_load_lds(                                                                             \
+        (const __attribute__((address_space(1))) void*)(k + (size_t)(ix)*ND + ((ld_chunk ^ ((ld_row + 16 * (j)) & 7)) * 8)), \
+        (__attribute__((address_space(3))) void*)&xs[buf][((j)*4 + wave) * 4 * NXROW], 16, 0, 0)
+#define LOOKM_LOAD_TILE(buf)                                   \
+    do {                                                       \
+        LOOKM_ROW_TO_LDS(ix0, 0, buf);                         \
+        LOOKM_ROW_TO_LDS(ix1, 1, buf);                         \
+        LOOKM_ROW_TO_LDS(ix2, 2, buf);                         \
+        LOOKM_ROW_TO_LDS(ix3, 3, buf);                         \
+        if (tid < NBX) stage_r = rnorm[ridx];                  \
     } while (0)
-#define LOOKM_STORE_TILE(buf)                                                                  \
-    do {                                                                                       \
-        *reinterpret_cast<uint4*>(&xs[buf][(ld_row)*NXSTRIDE + ld_chunk * 8]) = st0;           \
-        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 16) * NXSTRIDE + ld_chunk * 8]) = st1;    \
-        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 32) * NXSTRIDE + ld_chunk * 8]) = st2;    \
-        *reinterpret_cast<uint4*>(&xs[buf][(ld_row + 48) * NXSTRIDE + ld_chunk * 8]) = st3;    \
-        if (tid < NBX) xr[buf][tid] = stage_r;                                                 \
+#define LOOKM_STORE_TILE(buf)                                  \
+    do {                                                       \
+        if (tid < NBX) xr[buf][tid] = stage_r;                 \
     } while (0)
 
     // per stationary row of this lane; the initial state decodes to slot 0 with t = 0 (= cosine -1)
@@ -121,22 +123,24 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     int bxb[2] = {0, 0};            // slot of entry 0 of the block it came from
 
     LOOKM_LOAD_INDEX(x_begin);
-    LOOKM_LOAD_TILE();
+    LOOKM_LOAD_TILE(0);
     LOOKM_LOAD_INDEX(x_begin + NBX);     // clamped, so always in range
     LOOKM_STORE_TILE(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
     for (int it = 0; it < n_it; ++it) {
         const int buf = it & 1, x0 = x_begin + it * NBX;
         if (it + 1 < n_it) {
-            LOOKM_LOAD_TILE();                   // rows of tile it+1 (positions fetched one iteration ago)
+            LOOKM_LOAD_TILE(buf ^ 1);            // rows of tile it+1 (positions fetched one iteration ago)
             LOOKM_LOAD_INDEX(x0 + 2 * NBX);      // positions of tile it+2
         }
 #pragma unroll 1
         for (int rb = 0; rb < 2; ++rb) {
             nbf16x8 a[8];
-            const bf16_t* ap = &xs[buf][(rb * 32 + n) * NXSTRIDE + half * 8];
+            const bf16_t* ap = &xs[buf][(rb * 32 + n) * NXROW];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) a[ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + ks * 16));
+            for (int ks = 0; ks < 8; ++ks)
+                a[ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + (((2 * ks + half) ^ (n & 7)) * 8)));
             nf32x16 acc[2];
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }
@@ -174,8 +178,10 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             }
         }
         if (it + 1 < n_it) LOOKM_STORE_TILE(buf ^ 1);
+        __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the next tile's direct-to-LDS loads have landed
         __syncthreads();
     }
+#undef LOOKM_ROW_TO_LDS
 #undef LOOKM_LOAD_INDEX
 #undef LOOKM_LOAD_TILE
 #undef LOOKM_STORE_TILE
