@@ -61,6 +61,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_scores.restype = None
         L.oracle_scores_window.argtypes = [fp, fp, I, I, I, I, dp]
         L.oracle_scores_window.restype = None
+        L.oracle_scores_grouped.argtypes = [fp, fp, I, I, I, I, dp]
+        L.oracle_scores_grouped.restype = I
         L.oracle_decode.argtypes = [fp, fp, fp, I, I, I, I, dp]
         L.oracle_decode.restype = None
         L.oracle_row_lse.argtypes = [fp, fp, I, I, I, dp]
@@ -124,6 +126,38 @@ def scores(q, k) -> np.ndarray:
     out = np.empty((H, L), dtype=np.float64)
     lib().oracle_scores(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, L, d, _p(out, ctypes.c_double))
     return out[0] if single else out
+
+
+def scores_grouped(q, k) -> np.ndarray:
+    """Grouped-query attention: q [H, L, d], k [kv_heads, L, d] -> float64 [kv_heads, L], Eq. 4 summed over the query
+    heads that share a key head."""
+    q, k = as_f32(q), as_f32(k)
+    H, L, d = q.shape
+    kvh = k.shape[0]
+    out = np.empty((kvh, L), dtype=np.float64)
+    rc = lib().oracle_scores_grouped(_p(q, ctypes.c_float), _p(k, ctypes.c_float), H, kvh, L, d, _p(out, ctypes.c_double))
+    if rc != OK:
+        raise OracleError(rc)
+    return out
+
+
+def compress_grouped(q, k, v, mask, budget: int, recent_window: int, mode, rule="protect_text") -> dict:
+    """The whole path with grouped query heads: scores_grouped, then selection, matching and merging per KEY head
+    with the single-head functions above.  q: [H, L, d]; k, v: [kv_heads, L, d]."""
+    k32, v32 = as_f32(k), as_f32(v)
+    m = _mask(mask)
+    sc = scores_grouped(q, k)
+    kvh, L, d = k32.shape
+    B = int(budget)
+    out = dict(scores=sc, kept=np.empty((kvh, B), np.int32), evicted=np.empty((kvh, L - B), np.int32),
+               assign=np.empty((kvh, L - B), np.int32), sim=np.empty((kvh, L - B), np.float64),
+               k_out=np.empty((kvh, B, d), np.float64), v_out=np.empty((kvh, B, d), np.float64))
+    for h in range(kvh):
+        out["kept"][h], out["evicted"][h] = select(sc[h], m, B, recent_window, rule)
+        out["assign"][h], out["sim"][h] = nearest(k32[h], out["kept"][h], out["evicted"][h])
+        out["k_out"][h] = merge(k32[h], out["kept"][h], out["evicted"][h], out["assign"][h], out["sim"][h], mode)
+        out["v_out"][h] = merge(v32[h], out["kept"][h], out["evicted"][h], out["assign"][h], out["sim"][h], mode)
+    return out
 
 
 def scores_window(q, k, window: int) -> np.ndarray:

@@ -316,6 +316,28 @@ void oracle_scores(const float *q, const float *k, int H, int L, int d, double *
         oracle_scores_head(q + (size_t)h * L * d, k + (size_t)h * L * d, L, d, scores + (size_t)h * L);
 }
 
+/* Grouped-query attention: H query heads share kv_heads key heads, query head h reading key head h / (H / kv_heads).
+ * The paper omits head indices (Section 3.1) and evaluates multi-head models; with grouped heads one cache row serves a
+ * whole group, so its score is read as the SUM of Eq. 4 over the group's query heads.
+ * q: [H, L, d]; k: [kv_heads, L, d]; scores: [kv_heads, L].  Returns a negative code if kv_heads does not divide H. */
+int oracle_scores_grouped(const float *q, const float *k, int H, int kv_heads, int L, int d, double *scores)
+{
+    if (H <= 0 || kv_heads <= 0 || H % kv_heads != 0) return ORACLE_ERR_ARG;
+    const int group = H / kv_heads;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int kh = 0; kh < kv_heads; ++kh) {
+        double *one = (double *)malloc(sizeof(double) * (size_t)L);
+        double *acc = scores + (size_t)kh * L;
+        for (int j = 0; j < L; ++j) acc[j] = 0.0;
+        for (int m = 0; m < group; ++m) {          /* query heads kh*group .. kh*group + group - 1, in order */
+            scores_from_row(q + ((size_t)kh * group + m) * L * d, k + (size_t)kh * L * d, L, d, 0, one);
+            for (int j = 0; j < L; ++j) acc[j] += one[j];
+        }
+        free(one);
+    }
+    return ORACLE_OK;
+}
+
 void oracle_scores_window(const float *q, const float *k, int H, int L, int d, int window, double *scores)
 {
 #pragma omp parallel for schedule(dynamic, 1)

@@ -348,8 +348,9 @@ int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, voi
         if (hipEventCreate(&timer.ev[i]) != hipSuccess) return LOOKM_ERR_DEVICE;
     double sum[LOOKM_N_KERNELS] = {0};
     for (int r = 0; r < reps && rc == LOOKM_OK; ++r) {
-        // a kernel that is skipped for these sizes leaves its event at the previous kernel's time
-        for (int i = 0; i <= LOOKM_N_KERNELS; ++i) (void)hipEventRecord(timer.ev[i], timer.st);
+        // a kernel that is skipped for these sizes leaves its event at this early time (handled below); the
+        // start event goes last, so that the first kernel's interval does not contain the other records
+        for (int i = LOOKM_N_KERNELS; i >= 0; --i) (void)hipEventRecord(timer.ev[i], timer.st);
         lookm_host::g_timer = &timer;
         rc = enqueue_job(*job, timer.st);
         lookm_host::g_timer = nullptr;

@@ -42,6 +42,8 @@ MUTANTS = [
     ("window_one_row_short", "scores_from_row(q, k, L, d, L - window, scores);", "scores_from_row(q, k, L, d, L - window + 1, scores);"),
     ("decode_without_scale", "p[r] = dot / root_dim;", "p[r] = dot;"),
     ("decode_unnormalised", "out[c] += (p[r] / total) * (double)v[(size_t)r * d + c];", "out[c] += p[r] * (double)v[(size_t)r * d + c];"),
+    ("group_reads_wrong_key_head", "scores_from_row(q + ((size_t)kh * group + m) * L * d, k + (size_t)kh * L * d, L, d, 0, one);",
+     "scores_from_row(q + ((size_t)kh * group + m) * L * d, k + (size_t)m * L * d, L, d, 0, one);"),
     ("values_not_merged", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, mode, v_out", "r = oracle_merge_head(vh, d, kp, B, ev, Le, as, sm, 0, v_out"),
 ]
 

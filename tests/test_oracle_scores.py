@@ -204,3 +204,21 @@ def test_window_scores_special_cases():
     np.testing.assert_allclose(got, ref, rtol=1e-13)
     with pytest.raises(oracle.OracleError):
         oracle.scores_window(q, k, 0)
+
+
+# ---- grouped query heads: a key head's score is the sum over the query heads that read it ------------------------
+
+def test_grouped_scores():
+    rng = np.random.default_rng(21)
+    H, kvh, L, d = 6, 2, 45, 16
+    q = rng.standard_normal((H, L, d)).astype(np.float32)
+    k = rng.standard_normal((kvh, L, d)).astype(np.float32)
+    got = oracle.scores_grouped(q, k)
+    ref = np.stack([sum(dense_scores_numpy(q[kh * 3 + m], k[kh]) for m in range(3)) for kh in range(kvh)])
+    np.testing.assert_allclose(got, ref, rtol=1e-12)
+    np.testing.assert_allclose(got.sum(1), 3 * L, rtol=1e-12)                  # three softmax rows per position
+    np.testing.assert_array_equal(oracle.scores_grouped(q[:2], k), oracle.scores(q[:2], k))   # groups of one
+    twin = np.concatenate([q[:1], q[:1], q[1:2], q[1:2]])                      # identical query heads: twice the score
+    np.testing.assert_allclose(oracle.scores_grouped(twin, k), 2 * oracle.scores(q[:2], k), rtol=1e-14)
+    with pytest.raises(oracle.OracleError):
+        oracle.scores_grouped(q[:5], k)                                        # 5 heads do not split into 2 groups
