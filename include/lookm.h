@@ -204,6 +204,17 @@ int lookm_budget_from_ratios(int L, double alpha_recent, double alpha_important,
 int lookm_scores_window(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int window,
                         float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * Grouped query heads: H query heads in groups of H / kv_heads consecutive heads that share one key head (query head
+ * h reads key head h / (H / kv_heads)).  The paper omits head indices (Section 3.1); one cache row then serves a whole
+ * group, so its score is the sum of Eq. 4 over the group's query heads, and selection, matching and merging run once
+ * per key / value head.
+ *   q  device, [H, L, d];  k  device, [kv_heads, L, d];  scores_out  device, float [kv_heads, L].
+ *   kv_heads must divide H (else LOOKM_ERR_INVALID_ARG); size the workspace with lookm_workspace_bytes(H, ...).
+ */
+int lookm_scores_grouped(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt,
+                         float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* lookm_select under a chosen rule (lookm_select itself is LOOKM_SELECT_PROTECT_TEXT). */
 int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L,
                        int budget, int recent_window, lookm_select_rule rule,
@@ -225,6 +236,9 @@ typedef struct lookm_job {
     lookm_merge_mode merge_mode;
     lookm_select_rule rule;
     int score_window;                /* 0: Eq. 4 as printed (all query rows); w > 0: see lookm_scores_window */
+    int kv_heads;                    /* 0 (or H): one key / value head per query head.  Otherwise grouped query heads,
+                                        see lookm_scores_grouped: q and row_lse have H heads; k, v, k_out, v_out,
+                                        kept_idx and scores_out have kv_heads heads; kv_heads must divide H */
     void* k_out;
     void* v_out;
     int32_t* kept_idx;

@@ -15,12 +15,14 @@ struct Layout {
     size_t lse, scores, evicted, assign, sim, rnorm, plan, member_pos, member_w, partials, total;
 };
 
-Layout make_layout(int H, int L, int d, int dt, int budget)
+// Hq query heads, H key / value heads (Hq = H without grouped query heads): only the row log-sum-exp and the score
+// partials are per query head
+Layout make_layout(int Hq, int H, int L, int d, int dt, int budget)
 {
     const size_t HL = (size_t)H * L, HE = (size_t)H * (size_t)(L - budget);
     Layout w;
     size_t o = 0;
-    w.lse = o;     o += align_up(HL * sizeof(float));
+    w.lse = o;     o += align_up((size_t)Hq * L * sizeof(float));
     w.scores = o;  o += align_up(HL * sizeof(float));
     w.evicted = o; o += align_up(HE * sizeof(int32_t));
     w.assign = o;  o += align_up(HE * sizeof(int32_t));
@@ -31,7 +33,7 @@ Layout make_layout(int H, int L, int d, int dt, int budget)
     w.member_w = o;   o += align_up(HE * sizeof(float));
     // the score partials and the matching partials are never live at the same time: one slice serves both
     w.partials = o;
-    o += align_up(std::max(lookm_host::scores_scratch_floats(H, L, d, (lookm_dtype)dt) * sizeof(float),
+    o += align_up(std::max(lookm_host::scores_scratch_floats(Hq, L, d, (lookm_dtype)dt) * sizeof(float),
                            lookm_host::nearest_scratch_bytes(H, L, d, (lookm_dtype)dt, budget)));
     w.total = o;
     return w;
@@ -55,10 +57,10 @@ int check_budget(int L, int budget, int M)
     return LOOKM_OK;
 }
 
-int check_workspace(const void* ws, size_t bytes, int H, int L, int d, int dt, int budget)
+int check_workspace(const void* ws, size_t bytes, int Hq, int H, int L, int d, int dt, int budget)
 {
     if (ws == nullptr || (reinterpret_cast<uintptr_t>(ws) % kAlign) != 0) return LOOKM_ERR_WORKSPACE;
-    if (bytes < make_layout(H, L, d, dt, budget).total) return LOOKM_ERR_WORKSPACE;
+    if (bytes < make_layout(Hq, H, L, d, dt, budget).total) return LOOKM_ERR_WORKSPACE;
     return LOOKM_OK;
 }
 
@@ -96,42 +98,51 @@ int lookm_protected_count(const uint8_t* mask_host, int L, int recent_window)
 size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
 {
     if (check_shape(H, L, d, (int)dt) != LOOKM_OK || budget < 0 || budget > L) return 0;
-    return make_layout(H, L, d, (int)dt, budget).total;
+    return make_layout(H, H, L, d, (int)dt, budget).total;
 }
 
-static int scores_impl(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
-                       int window, float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+static int scores_impl(const void* q, const void* k, const float* row_lse, int H, int kv_heads, int L, int d,
+                       lookm_dtype dt, int window, float* scores_out, void* workspace, size_t workspace_bytes,
+                       void* hip_stream)
 {
     if (!q || !k || !scores_out) return LOOKM_ERR_INVALID_ARG;
     int rc = check_shape(H, L, d, (int)dt);
     if (rc != LOOKM_OK) return rc;
+    if (kv_heads <= 0 || H % kv_heads != 0) return LOOKM_ERR_INVALID_ARG;
     if (window < 0 || window > L) return LOOKM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(scores_out)) return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, 0);
+    rc = check_workspace(workspace, workspace_bytes, H, kv_heads, L, d, (int)dt, 0);
     if (rc != LOOKM_OK) return rc;
-    const Layout w = make_layout(H, L, d, (int)dt, 0);
-    return lookm_host::launch_scores(q, k, H, L, d, dt, window ? L - window : 0, at<float>(workspace, w.lse), row_lse,
-                                     scores_out, nullptr, at<float>(workspace, w.partials), (hipStream_t)hip_stream);
+    const Layout w = make_layout(H, kv_heads, L, d, (int)dt, 0);
+    return lookm_host::launch_scores(q, k, H, kv_heads, L, d, dt, window ? L - window : 0, at<float>(workspace, w.lse),
+                                     row_lse, scores_out, nullptr, at<float>(workspace, w.partials),
+                                     (hipStream_t)hip_stream);
 }
 
 int lookm_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, float* scores_out,
                  void* workspace, size_t workspace_bytes, void* hip_stream)
 {
-    return scores_impl(q, k, nullptr, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
+    return scores_impl(q, k, nullptr, H, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_scores_lse(const void* q, const void* k, const float* row_lse, int H, int L, int d, lookm_dtype dt,
                      float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!row_lse) return LOOKM_ERR_INVALID_ARG;
-    return scores_impl(q, k, row_lse, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
+    return scores_impl(q, k, row_lse, H, H, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_scores_window(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int window,
                         float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (window <= 0) return LOOKM_ERR_INVALID_ARG;
-    return scores_impl(q, k, nullptr, H, L, d, dt, window, scores_out, workspace, workspace_bytes, hip_stream);
+    return scores_impl(q, k, nullptr, H, H, L, d, dt, window, scores_out, workspace, workspace_bytes, hip_stream);
+}
+
+int lookm_scores_grouped(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt,
+                         float* scores_out, void* workspace, size_t workspace_bytes, void* hip_stream)
+{
+    return scores_impl(q, k, nullptr, H, kv_heads, L, d, dt, 0, scores_out, workspace, workspace_bytes, hip_stream);
 }
 
 int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H, int L, int budget,
@@ -179,9 +190,9 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
     if (budget < 1 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
     if (budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;   // empty lists may be NULL
     if (!aligned16(k)) return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
+    rc = check_workspace(workspace, workspace_bytes, H, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
-    const Layout w = make_layout(H, L, d, (int)dt, budget);
+    const Layout w = make_layout(H, H, L, d, (int)dt, budget);
     return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
                                       false, assign, sim, at<void>(workspace, w.partials), (hipStream_t)hip_stream);
 }
@@ -199,9 +210,9 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
     if (budget < 0 || budget > L) return LOOKM_ERR_BUDGET_RANGE;
     if (merge_mode != LOOKM_MERGE_NONE && budget < L && (!evicted_idx || !assign || !sim)) return LOOKM_ERR_INVALID_ARG;
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out)) return LOOKM_ERR_INVALID_ARG;
-    rc = check_workspace(workspace, workspace_bytes, H, L, d, (int)dt, budget);
+    rc = check_workspace(workspace, workspace_bytes, H, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
-    const Layout w = make_layout(H, L, d, (int)dt, budget);
+    const Layout w = make_layout(H, H, L, d, (int)dt, budget);
     return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
                                     at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
@@ -215,6 +226,7 @@ static int validate_job(const lookm_job& j)
     if ((int)j.merge_mode < LOOKM_MERGE_NONE || (int)j.merge_mode > LOOKM_MERGE_WEIGHTED) return LOOKM_ERR_INVALID_ARG;
     if ((int)j.rule < LOOKM_SELECT_PROTECT_TEXT || (int)j.rule > LOOKM_SELECT_LITERAL) return LOOKM_ERR_INVALID_ARG;
     if (j.score_window < 0 || j.score_window > j.L) return LOOKM_ERR_INVALID_ARG;
+    if (j.kv_heads < 0 || (j.kv_heads > 0 && (j.H <= 0 || j.H % j.kv_heads != 0))) return LOOKM_ERR_INVALID_ARG;
     int rc = check_shape(j.H, j.L, j.d, (int)j.dt);
     if (rc != LOOKM_OK) return rc;
     rc = check_budget(j.L, j.budget, j.recent_window);
@@ -222,16 +234,18 @@ static int validate_job(const lookm_job& j)
     if (!aligned16(j.q) || !aligned16(j.k) || !aligned16(j.v) || !aligned16(j.k_out) || !aligned16(j.v_out) ||
         (j.scores_out && !aligned16(j.scores_out)) || (j.row_lse && !aligned16(j.row_lse)))
         return LOOKM_ERR_INVALID_ARG;
-    return check_workspace(j.workspace, j.workspace_bytes, j.H, j.L, j.d, (int)j.dt, j.budget);
+    return check_workspace(j.workspace, j.workspace_bytes, j.H, j.kv_heads ? j.kv_heads : j.H, j.L, j.d, (int)j.dt,
+                           j.budget);
 }
 
 // the launch sequence of one validated job
 static int enqueue_job(const lookm_job& j, hipStream_t st)
 {
-    const int H = j.H, L = j.L, d = j.d, budget = j.budget;
+    // Hq query heads; everything after the scores runs per key / value head
+    const int Hq = j.H, H = j.kv_heads ? j.kv_heads : j.H, L = j.L, d = j.d, budget = j.budget;
     const lookm_dtype dt = j.dt;
     void* workspace = j.workspace;
-    const Layout w = make_layout(H, L, d, (int)dt, budget);
+    const Layout w = make_layout(Hq, H, L, d, (int)dt, budget);
     float* scores = j.scores_out ? j.scores_out : at<float>(workspace, w.scores);
     int32_t* evicted = at<int32_t>(workspace, w.evicted);
     int32_t* assign = at<int32_t>(workspace, w.assign);
@@ -240,7 +254,7 @@ static int enqueue_job(const lookm_job& j, hipStream_t st)
     // the matching needs the inverse key norms; the matrix-core score pass writes them from the key rows it holds
     const bool match = j.merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
     float* rnorm = at<float>(workspace, w.rnorm);
-    int rc = lookm_host::launch_scores(j.q, j.k, H, L, d, dt, j.score_window ? L - j.score_window : 0,
+    int rc = lookm_host::launch_scores(j.q, j.k, Hq, H, L, d, dt, j.score_window ? L - j.score_window : 0,
                                        at<float>(workspace, w.lse), j.row_lse, scores,
                                        match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
     if (rc != LOOKM_OK) return rc;
@@ -268,7 +282,7 @@ static int compress_impl(const void* q, const void* k, const void* v, const uint
     j.q = q; j.k = k; j.v = v; j.modality_mask = modality_mask; j.row_lse = row_lse;
     j.H = H; j.L = L; j.d = d; j.dt = dt;
     j.budget = budget; j.recent_window = recent_window; j.merge_mode = merge_mode; j.rule = LOOKM_SELECT_PROTECT_TEXT;
-    j.score_window = 0;
+    j.score_window = 0; j.kv_heads = 0;
     j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
     j.workspace = workspace; j.workspace_bytes = workspace_bytes;
     const int rc = validate_job(j);
@@ -376,7 +390,7 @@ int lookm_compress_profile(const void* q, const void* k, const void* v, const ui
     j.q = q; j.k = k; j.v = v; j.modality_mask = modality_mask; j.row_lse = nullptr;
     j.H = H; j.L = L; j.d = d; j.dt = dt;
     j.budget = budget; j.recent_window = recent_window; j.merge_mode = merge_mode; j.rule = LOOKM_SELECT_PROTECT_TEXT;
-    j.score_window = 0;
+    j.score_window = 0; j.kv_heads = 0;
     j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
     j.workspace = workspace; j.workspace_bytes = workspace_bytes;
     return lookm_job_profile(&j, reps, kernel_ms_host, hip_stream);

@@ -77,8 +77,10 @@ namespace lookm_host {
 // lse_in: optional caller-supplied natural-log row log-sum-exp [H, L]; when given, pass 1 is skipped
 // rnorm: optional [H, L]; the matrix-core path (see scores_write_rnorm) fills it with 1/||k row|| on the way
 // first_row: only the query rows first_row .. L-1 are summed (0 = all rows, Eq. 4 as printed)
-int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int first_row, float* lse,
-                  const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st);
+// H query heads in groups of H / kv_heads that read one key head each (kv_heads = H: plain multi-head attention);
+// lse, lse_in: [H, L]; scores, rnorm: [kv_heads, L]
+int launch_scores(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt, int first_row,
+                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st);
 inline bool scores_write_rnorm(int d, lookm_dtype dt) { return dt == LOOKM_BF16 && d == 128; }
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int rule, int32_t* kept,

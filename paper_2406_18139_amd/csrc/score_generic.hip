@@ -42,8 +42,9 @@ __device__ __forceinline__ void tile_dot(const float* qt, const float* kt, int d
 }
 
 template <typename T>
-__global__ void __launch_bounds__(256) k_score_lse_generic(const T* __restrict__ q, const T* __restrict__ k, int L,
-                                                           int R0, int d, float scale2, float* __restrict__ lse2)
+__global__ void __launch_bounds__(256) k_score_lse_generic(const T* __restrict__ q, const T* __restrict__ k, int group,
+                                                           int L, int R0, int d, float scale2,
+                                                           float* __restrict__ lse2)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     float* qt = smem;
@@ -51,9 +52,9 @@ __global__ void __launch_bounds__(256) k_score_lse_generic(const T* __restrict__
     const int nb = (L + TS - 1) / TS;
     const int ib = nb - 1 - (int)blockIdx.x;  // longest strips first
     if ((ib + 1) * TS <= R0) return;          // no query row of this strip counts (observation window)
-    const int h = blockIdx.y;
+    const int h = blockIdx.y;                 // query head; `group` consecutive query heads read key head h / group
     q += (size_t)h * L * d;
-    k += (size_t)h * L * d;
+    k += (size_t)(h / group) * L * d;
     const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
 
     stage_tile(q, ib * TS, L, d, qt);
@@ -106,8 +107,9 @@ __global__ void __launch_bounds__(256) k_score_lse_generic(const T* __restrict__
 }
 
 template <typename T>
-__global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restrict__ q, const T* __restrict__ k, int L,
-                                                              int R0, int d, float scale2, const float* __restrict__ lse2,
+__global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restrict__ q, const T* __restrict__ k, int group,
+                                                              int L, int R0, int d, float scale2,
+                                                              const float* __restrict__ lse2,
                                                               float lse_scale, float* __restrict__ scores)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
@@ -115,14 +117,15 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
     float* kt = smem + (size_t)d * TS;
     const int nb = (L + TS - 1) / TS;
     const int jb = blockIdx.x;  // column strip 0 is the longest
-    const int h = blockIdx.y;
-    q += (size_t)h * L * d;
+    const int h = blockIdx.y;                 // key head: the column sums of its `group` query heads are added up
+    q += (size_t)h * group * L * d;
     k += (size_t)h * L * d;
-    lse2 += (size_t)h * L;
+    lse2 += (size_t)h * group * L;
     const int ty = threadIdx.x / 16, tx = threadIdx.x % 16;
 
     stage_tile(k, jb * TS, L, d, kt);
     float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < group; ++m, q += (size_t)L * d, lse2 += L)
     for (int ib = max(jb, R0 / TS); ib < nb; ++ib) {   // query rows before R0 do not count
         __syncthreads();
         stage_tile(q, ib * TS, L, d, qt);
@@ -157,14 +160,15 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
 
 namespace lookm_host {
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, int R0, float* lse, const float* lse_in,
-                       float* scores, float* rnorm, float* scratch, hipStream_t st);
+int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L, int d, int R0, float* lse,
+                       const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st);
 size_t scores_mfma_scratch_floats(int H, int L);
 
 template <typename T>
-static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, int R0, float* lse, const float* lse_in,
-                                 float* scores, hipStream_t st)
+static int launch_scores_generic(const T* q, const T* k, int H, int kv_heads, int L, int d, int R0, float* lse,
+                                 const float* lse_in, float* scores, hipStream_t st)
 {
+    const int group = H / kv_heads;
     const int nb = (L + lookm::TS - 1) / lookm::TS;
     size_t lds = (size_t)2 * d * lookm::TS * sizeof(float);
     if (lds < 8192) lds = 8192;   // the final cross-thread combine reuses the tile buffers
@@ -180,11 +184,11 @@ static int launch_scores_generic(const T* q, const T* k, int H, int L, int d, in
         attr_done = true;
     }
     if (!lse_in) {
-        hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, L, R0, d, scale2, lse);
+        hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, group, L, R0, d, scale2, lse);
         mark(LOOKM_K_SCORE_LSE);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
-    hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, grid, block, lds, st, q, k, L, R0, d, scale2,
+    hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, dim3(nb, kv_heads), block, lds, st, q, k, group, L, R0, d, scale2,
                        lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, scores);
     mark(LOOKM_K_SCORE_COLSUM);
     return hip_ok(hipGetLastError());
@@ -195,17 +199,17 @@ size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)
     return (dt == LOOKM_BF16 && d == 128) ? scores_mfma_scratch_floats(H, L) : 0;
 }
 
-int launch_scores(const void* q, const void* k, int H, int L, int d, lookm_dtype dt, int first_row, float* lse,
-                  const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
+int launch_scores(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt, int first_row,
+                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     const int R0 = first_row;
     if (dt == LOOKM_BF16) {
         if (scores_write_rnorm(d, dt))
-            return launch_scores_mfma(q, k, H, L, d, R0, lse, lse_in, scores, rnorm, scratch, st);
-        return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, L, d, R0, lse, lse_in, scores,
-                                     st);
+            return launch_scores_mfma(q, k, H, kv_heads, L, d, R0, lse, lse_in, scores, rnorm, scratch, st);
+        return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, kv_heads, L, d, R0, lse, lse_in,
+                                     scores, st);
     }
-    return launch_scores_generic((const float*)q, (const float*)k, H, L, d, R0, lse, lse_in, scores, st);
+    return launch_scores_generic((const float*)q, (const float*)k, H, kv_heads, L, d, R0, lse, lse_in, scores, st);
 }
 
 }  // namespace lookm_host

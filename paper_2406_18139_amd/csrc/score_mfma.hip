@@ -102,8 +102,8 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT, int 
 //   zero key) for the matching of Eq. 9, from the registers it holds anyway - the keys are not read again for it.
 template <int PASS>
 __global__ void __launch_bounds__(256, 3)
-k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int L, int R0, float scale2, int C,
-             int U, const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a,
+k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int group, int L, int R0, float scale2,
+             int C, int U, const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a,
              float* __restrict__ part_b, float* __restrict__ rnorm)
 {
     __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
@@ -134,8 +134,11 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     const int s0 = tile * BS;
     const int n_chunks_total = (L + CT - 1) / CT;
     const int u = g * nS + tile;               // slot of this (chunk, strip) in the partial arrays [h][chunk][strip][256]
-    const bf16_t* S = ((PASS == 1) ? q : k) + (size_t)h * L * SD;   // stationary tensor
-    const bf16_t* X = ((PASS == 1) ? k : q) + (size_t)h * L * SD;   // streamed tensor
+    // h runs over the query heads; with grouped query heads, `group` consecutive ones read key head h / group
+    const bf16_t* qh = q + (size_t)h * L * SD;
+    const bf16_t* kh = k + (size_t)(h / group) * L * SD;
+    const bf16_t* S = (PASS == 1) ? qh : kh;   // stationary tensor
+    const bf16_t* X = (PASS == 1) ? kh : qh;   // streamed tensor
     const float* lse_h = lse2 + (size_t)h * L;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, n = lane & 31;
@@ -190,7 +193,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     load_tile(x_begin, 0);
     store_tile(0);
-    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0)) {
+    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0) && h % group == 0) {
         // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
         // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
         // partial sums, number p over groups p and p + 8, then a pairwise tree), so both give the same bits
@@ -219,7 +222,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             for (int j = 0; j < 4; ++j) pair[j] = part[j] + __shfl_xor(part[j], 32);
             const float ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
             const int row = w0 + cb * 32 + n;
-            if (half == 0 && row < L) rnorm[(size_t)h * L + row] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
+            if (half == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
@@ -299,11 +302,12 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     }
 }
 
-// Folds the chunks of every strip, in chunk order: pass 1 -> lse2[h, i] = log2 sum_j 2^(c q_i.k_j);
-// pass 2 -> scores[h, j] = A_s[j].  One thread per (head, row).
+// Folds the chunks of every strip, in chunk order: pass 1 -> lse2[h, i] = log2 sum_j 2^(c q_i.k_j) per query
+// head; pass 2 -> scores[h, j] = A_s[j] per key head, the partials of its `group` query heads added in head
+// order (group = 1: one query head per key head).  One thread per (head, row).
 template <int PASS>
 __global__ void __launch_bounds__(256)
-k_score_combine(int H, int L, int R0, int C, const float* __restrict__ part_a, const float* __restrict__ part_b,
+k_score_combine(int group, int L, int R0, int C, const float* __restrict__ part_a, const float* __restrict__ part_b,
                 float* __restrict__ out)
 {
     const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
@@ -313,8 +317,9 @@ k_score_combine(int H, int L, int R0, int C, const float* __restrict__ part_a, c
     const int g0 = first_chunk(PASS, tile, CT, R0), nc = strip_chunks(PASS, tile, L, CT, R0);
     if (nc == 0) return;     // pass 1 under a window: a strip with no row that counts (its values are never read)
     const size_t stride = (size_t)nS * BS;      // from one chunk of a strip to the next
-    const float* pa = part_a + (((size_t)h * G + g0) * nS + tile) * BS + r;
-    const float* pb = part_b + (((size_t)h * G + g0) * nS + tile) * BS + r;
+    const int h_first = (PASS == 1) ? h : h * group;      // first query head whose partials are read
+    const float* pa = part_a + (((size_t)h_first * G + g0) * nS + tile) * BS + r;
+    const float* pb = part_b + (((size_t)h_first * G + g0) * nS + tile) * BS + r;
     if (PASS == 1) {
         float M = -1e30f;
         for (int c = 0; c < nc; ++c) M = fmaxf(M, pa[c * stride]);
@@ -323,7 +328,8 @@ k_score_combine(int H, int L, int R0, int C, const float* __restrict__ part_a, c
         out[(size_t)h * L + row] = M + log2f(Ls);
     } else {
         float sum = 0.f;
-        for (int c = 0; c < nc; ++c) sum += pa[c * stride];
+        for (int m = 0; m < group; ++m)
+            for (int c = 0; c < nc; ++c) sum += pa[((size_t)m * G + c) * stride];
         out[(size_t)h * L + row] = sum;
     }
 }
@@ -369,10 +375,11 @@ size_t scores_mfma_scratch_floats(int H, int L)
     return (size_t)2 * H * G * nS * lookm::BS;
 }
 
-int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, int R0, float* lse, const float* lse_in,
-                       float* scores, float* rnorm, float* scratch, hipStream_t st)
+int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L, int d, int R0, float* lse,
+                       const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
+    const int group = H / kv_heads;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     const int C = chunk_tiles(H, L);
     // the chunk length is the full problem's also under a window, so the partial arrays keep their layout and size
@@ -384,17 +391,18 @@ int launch_scores_mfma(const void* q, const void* k, int H, int L, int d, int R0
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
     if (!lse_in) {
-        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, L, R0, scale2,
-                           C, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
+        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, group, L, R0,
+                           scale2, C, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
         mark(LOOKM_K_SCORE_LSE);
-        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, H, L, R0, C, part_a, part_b, lse);
+        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, 1, L, R0, C, part_a, part_b, lse);
         mark(LOOKM_K_SCORE_LSE_FOLD);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
-    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, L, R0, scale2, C,
-                       U2, lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
+    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, group, L, R0, scale2,
+                       C, U2, lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
     mark(LOOKM_K_SCORE_COLSUM);
-    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, H), dim3(256), 0, st, H, L, R0, C, part_a, part_b, scores);
+    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, kv_heads), dim3(256), 0, st, group, L, R0, C, part_a, part_b,
+                       scores);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);
     return hip_ok(hipGetLastError());
 }

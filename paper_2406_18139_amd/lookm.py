@@ -33,7 +33,7 @@ EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "loo
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
            "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile", "lookm_decode_workspace_bytes",
-           "lookm_decode_attention"]
+           "lookm_decode_attention", "lookm_scores_grouped"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -45,7 +45,7 @@ class Job(ctypes.Structure):
                 ("modality_mask", ctypes.c_void_p), ("row_lse", ctypes.c_void_p),
                 ("H", ctypes.c_int), ("L", ctypes.c_int), ("d", ctypes.c_int), ("dt", ctypes.c_int),
                 ("budget", ctypes.c_int), ("recent_window", ctypes.c_int), ("merge_mode", ctypes.c_int),
-                ("rule", ctypes.c_int), ("score_window", ctypes.c_int),
+                ("rule", ctypes.c_int), ("score_window", ctypes.c_int), ("kv_heads", ctypes.c_int),
                 ("k_out", ctypes.c_void_p), ("v_out", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
                 ("scores_out", ctypes.c_void_p), ("status_out", ctypes.c_void_p),
                 ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t)]
@@ -97,6 +97,8 @@ def lib() -> ctypes.CDLL:
         L.lookm_budget_from_ratios.argtypes = [I, ctypes.c_double, ctypes.c_double, ctypes.POINTER(I), ctypes.POINTER(I)]
         L.lookm_select_rule_.restype = I
         L.lookm_select_rule_.argtypes = [vp, vp, I, I, I, I, I, vp, vp, vp, vp]
+        L.lookm_scores_grouped.restype = I
+        L.lookm_scores_grouped.argtypes = [vp, vp, I, I, I, I, I, vp, vp, sz, vp]
         L.lookm_scores_window.restype = I
         L.lookm_scores_window.argtypes = [vp, vp, I, I, I, I, I, vp, vp, sz, vp]
         L.lookm_decode_workspace_bytes.restype = sz
@@ -199,12 +201,13 @@ def lookm_compress(q, k, v, modality_mask, budget: int, recent_window: int, merg
     """One layer's compression.  q, k, v: GPU tensors [H, L, d]; modality_mask: GPU uint8 [L].
     ``check=True`` synchronises to read the device status word and raises on failure.
     With ``row_lse`` (GPU float32 [H, L]) the call forwards to lookm_compress_lse; with a selection rule other
-    than the default, or an observation window for the scores, it forwards to lookm_compress_batch as a single job
-    (the entry point that takes them)."""
-    if _rule(rule) != 0 or int(score_window) != 0:
+    than the default, an observation window for the scores, or fewer key / value heads than query heads (grouped
+    query heads: k, v [kv_heads, L, d]), it forwards to lookm_compress_batch as a single job (the entry point that
+    takes them)."""
+    if _rule(rule) != 0 or int(score_window) != 0 or k.shape[0] != q.shape[0]:
         H, L, d = q.shape
         if out is None:
-            out = alloc_outputs(H, L, d, int(budget), q.dtype, q.device, want_scores)
+            out = alloc_outputs(k.shape[0], L, d, int(budget), q.dtype, q.device, want_scores)
         if workspace is None:
             workspace = alloc_workspace(H, L, d, min(max(int(budget), 0), L), _dt(q), q.device)
         lookm_compress_batch([make_job(q, k, v, modality_mask, budget, recent_window, merge_mode, out, workspace,
@@ -250,10 +253,12 @@ def make_job(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode
     H, L, d = q.shape
     if row_lse is not None and (row_lse.dtype != torch.float32 or tuple(row_lse.shape) != (H, L)):
         raise ValueError("row_lse must be float32 [H, L]")
+    kv_heads = 0 if k.shape[0] == H else int(k.shape[0])        # grouped query heads when k has fewer heads than q
     wp, wn = _ws_ptr(workspace)
     return Job(_dev(q, "q"), _dev(k, "k"), _dev(v, "v"), _dev(modality_mask, "modality_mask"),
                _dev(row_lse, "row_lse") if row_lse is not None else None, H, L, d, _dt(q), int(budget),
-               int(recent_window), _mode(merge_mode), _rule(rule), int(score_window), _dev(out.k_out, "k_out"),
+               int(recent_window), _mode(merge_mode), _rule(rule), int(score_window), kv_heads,
+               _dev(out.k_out, "k_out"),
                _dev(out.v_out, "v_out"),
                _dev(out.kept_idx, "kept_idx"), _dev(out.scores, "scores") if out.scores is not None else None,
                _dev(out.status, "status"), wp, wn)
@@ -334,6 +339,21 @@ def lookm_scores(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor
     rc = lib().lookm_scores(_dev(q, "q"), _dev(k, "k"), H, L, d, dt, scores.data_ptr(), wp, wn, _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_scores")
+    return scores
+
+
+def lookm_scores_grouped(q, k, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q: [H, L, d], k: [kv_heads, L, d] -> scores [kv_heads, L] (Eq. 4 summed over each key head's query heads)."""
+    H, L, d = q.shape
+    kvh = k.shape[0]
+    dt = _dt(q)
+    scores = torch.empty((kvh, L), dtype=torch.float32, device=q.device)
+    if workspace is None:
+        workspace = alloc_workspace(H, L, d, 0, dt, q.device)
+    wp, wn = _ws_ptr(workspace)
+    rc = lib().lookm_scores_grouped(_dev(q, "q"), _dev(k, "k"), H, kvh, L, d, dt, scores.data_ptr(), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_scores_grouped")
     return scores
 
 

@@ -87,6 +87,7 @@ def test_stage_calls_reject_bad_arguments():
     assert L.lookm_scores(FAKE, FAKE, 1, 8, 12, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_UNSUPPORTED
     assert L.lookm_scores(FAKE, FAKE, 1, 8, 8, 0, FAKE, FAKE, 8, None) == lookm.ERR_WORKSPACE
     assert L.lookm_scores_lse(FAKE, FAKE, None, 1, 8, 8, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
+    assert L.lookm_scores_grouped(FAKE, FAKE, 6, 4, 8, 8, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_scores_window(FAKE, FAKE, 1, 8, 8, 0, 0, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_scores_window(FAKE, FAKE, 1, 8, 8, 0, 9, FAKE, FAKE, 1 << 20, None) == lookm.ERR_INVALID_ARG
     assert L.lookm_compress_lse(FAKE, FAKE, FAKE, FAKE, None, 2, 64, 64, 0, 32, 8, 1, FAKE, FAKE, FAKE, None, FAKE, FAKE,
@@ -101,7 +102,7 @@ def test_stage_calls_reject_bad_arguments():
 
 def fake_job(**kw):
     f = dict(q=FAKE, k=FAKE, v=FAKE, modality_mask=FAKE, row_lse=None, H=2, L=64, d=64, dt=0, budget=32, recent_window=8,
-             merge_mode=1, rule=0, score_window=0, k_out=FAKE, v_out=FAKE, kept_idx=FAKE, scores_out=None, status_out=FAKE,
+             merge_mode=1, rule=0, score_window=0, kv_heads=0, k_out=FAKE, v_out=FAKE, kept_idx=FAKE, scores_out=None, status_out=FAKE,
              workspace=FAKE, workspace_bytes=1 << 30)
     f.update(kw)
     return lookm.Job(**f)
@@ -123,6 +124,7 @@ def test_batch_validates_every_job_before_any_launch():
     assert run([fake_job(rule=5)]) == lookm.ERR_INVALID_ARG
     assert run([fake_job(budget=99)]) == lookm.ERR_BUDGET_RANGE
     assert run([fake_job(score_window=65)]) == lookm.ERR_INVALID_ARG
+    assert run([fake_job(H=6, kv_heads=4)]) == lookm.ERR_INVALID_ARG          # 4 key heads do not divide 6 query heads
     assert run([fake_job(row_lse=FAKE + 2)]) == lookm.ERR_INVALID_ARG
     # the struct's last field: a layout that disagreed with the header would report something else
     assert run([fake_job(workspace_bytes=64)]) == lookm.ERR_WORKSPACE and bad.value == 0

@@ -226,3 +226,30 @@ def test_compress_with_an_observation_window():
     for h in range(2):
         parity.check_merge(k[h].float().numpy(), kept[h], ev[h].cpu().numpy(), a[h].cpu().numpy(), s[h].cpu().numpy(),
                            "pivotal", res.k_out[h].float().cpu().numpy(), torch.bfloat16)
+
+
+def test_compress_with_grouped_query_heads():
+    # 8 query heads on 2 key / value heads, 7B-shaped prompt; oracle = grouped scores + the single-head stages
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w, heads=list(range(8)))
+    k, v = k[[0, 4]].contiguous(), v[[0, 4]].contiguous()
+    B, M = w.budget(), w.M
+    res = lookm.lookm_compress(q.cuda(), k.cuda(), v.cuda(), mask.cuda(), B, M, "weighted", want_scores=True)
+    assert res.k_out.shape == (2, B, w.d) and res.kept_idx.shape == (2, B)
+    ref = oracle.compress_grouped(q, k, v, mask, B, M, "weighted")
+    sg = res.scores.cpu().numpy().astype(np.float64)
+    kept = res.kept_idx.cpu().numpy()
+    mask_np = mask.numpy()
+    for h in range(2):
+        parity.check_scores(sg[h], ref["scores"][h])
+    diff = parity.check_kept(kept, sg, ref["scores"], ref["kept"], mask_np, B, M)
+    assert diff <= 1
+    ev = torch.from_numpy(np.stack([np.setdiff1d(np.arange(w.L, dtype=np.int32), kept[h]) for h in range(2)])).cuda()
+    a, s = lookm.lookm_nearest(k.cuda(), res.kept_idx, ev)
+    for h in range(2):
+        evh, ah, sh = ev[h].cpu().numpy(), a[h].cpu().numpy(), s[h].cpu().numpy()
+        parity.check_nearest(k[h].float().numpy(), kept[h], evh, ah, sh)
+        parity.check_merge(k[h].float().numpy(), kept[h], evh, ah, sh, "weighted", res.k_out[h].float().cpu().numpy(),
+                           torch.bfloat16)
+        parity.check_merge(v[h].float().numpy(), kept[h], evh, ah, sh, "weighted", res.v_out[h].float().cpu().numpy(),
+                           torch.bfloat16)

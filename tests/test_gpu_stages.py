@@ -95,6 +95,25 @@ def test_window_scores_match_oracle(H, L, d, dtype, windows):
     assert torch.equal(lookm.lookm_scores_window(qg, kg, L), full)       # the whole prompt: the same launches
 
 
+@pytest.mark.parametrize("H,kvh,L,d,dtype", [
+    (8, 2, 700, 128, torch.bfloat16),       # matrix cores, groups of four
+    (6, 3, 1500, 128, torch.bfloat16),
+    (4, 1, 300, 64, torch.bfloat16),        # portable kernels, one key head for all query heads
+    (4, 2, 256, 64, torch.float32),
+])
+def test_grouped_scores_match_oracle(H, kvh, L, d, dtype):
+    g = torch.Generator().manual_seed(H * 100 + L)
+    q = torch.randn(H, L, d, generator=g).to(dtype)
+    k = torch.randn(kvh, L, d, generator=g).to(dtype)
+    s = lookm.lookm_scores_grouped(q.cuda(), k.cuda()).cpu().numpy().astype(np.float64)
+    ref = oracle.scores_grouped(q, k)
+    np.testing.assert_allclose(s, ref, rtol=2e-5)
+    # the same sum taken from single-head launches: one query head per key head, repeated keys
+    grp = H // kvh
+    single = lookm.lookm_scores(q.cuda(), k.repeat_interleave(grp, 0).cuda()).view(kvh, grp, L)
+    np.testing.assert_allclose(s, single.double().sum(1).cpu().numpy(), rtol=1e-6)
+
+
 def select_case(scores, mask, B, M):
     sg = torch.from_numpy(np.asarray(scores, np.float32)).cuda()
     mg = torch.from_numpy(np.asarray(mask, np.uint8)).cuda()
