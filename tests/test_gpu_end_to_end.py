@@ -253,3 +253,43 @@ def test_compress_with_grouped_query_heads():
                            torch.bfloat16)
         parity.check_merge(v[h].float().numpy(), kept[h], evh, ah, sh, "weighted", res.v_out[h].float().cpu().numpy(),
                            torch.bfloat16)
+
+
+def test_maximum_length():
+    # L = LOOKM_MAX_L: the oracle cannot afford the whole L x L problem, so scores are checked on sampled columns
+    # (computed one by one from the definition), everything after the scores stage by stage on the kernel's own data
+    H, L, d, M, B = 2, 32768, 128, 64, 4000
+    rng = np.random.default_rng(99)
+    g = torch.Generator().manual_seed(99)
+    q = torch.randn(H, L, d, generator=g).to(torch.bfloat16)
+    k = torch.randn(H, L, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(H, L, d, generator=g).to(torch.bfloat16)
+    mask_np = (rng.random(L) < 0.93).astype(np.uint8)
+    assert oracle.protected_count(mask_np, M) < B
+    res = lookm.lookm_compress(q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(mask_np).cuda(), B, M, "averaged",
+                               want_scores=True)
+    sg = res.scores.cpu().numpy().astype(np.float64)
+    kept = res.kept_idx.cpu().numpy()
+    np.testing.assert_allclose(sg.sum(1), L, rtol=2e-5)
+    # columns j >= L - 192 only receive attention from the rows i >= j: 192 full softmax rows in binary64
+    q64, k64 = q[0].double().numpy(), k[0].double().numpy()
+    rows = np.arange(L - 192, L)
+    logits = (q64[rows] @ k64.T) / np.sqrt(d)
+    logits[np.arange(L)[None, :] > rows[:, None]] = -np.inf
+    p = np.exp(logits - logits.max(1, keepdims=True))
+    p /= p.sum(1, keepdims=True)
+    for j in (L - 1, L - 7, L - 64, L - 129, L - 192):
+        ref = p[rows >= j, j].sum()
+        assert abs(sg[0, j] - ref) <= 2e-5 * ref, (j, sg[0, j], ref)
+    for h in range(H):
+        assert kept[h].tolist() == oracle.select(sg[h], mask_np, B, M)[0].tolist()
+    ev = torch.from_numpy(np.stack([np.setdiff1d(np.arange(L, dtype=np.int32), kept[h]) for h in range(H)])).cuda()
+    a, s = lookm.lookm_nearest(k.cuda(), res.kept_idx, ev)
+    a, s, evn = a.cpu().numpy(), s.cpu().numpy(), ev.cpu().numpy()
+    kf = k.float().numpy()
+    pick = rng.choice(L - B, 300, replace=False)                      # 300 of the 28 768 evicted keys of head 1
+    parity.check_nearest(kf[1], kept[1], evn[1][pick], a[1][pick], s[1][pick])
+    for h in range(H):
+        parity.check_merge(kf[h], kept[h], evn[h], a[h], s[h], "averaged", res.k_out[h].float().cpu().numpy(), torch.bfloat16)
+        parity.check_merge(v[h].float().numpy(), kept[h], evn[h], a[h], s[h], "averaged", res.v_out[h].float().cpu().numpy(),
+                           torch.bfloat16)
