@@ -276,7 +276,8 @@ int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cac
 /* ---- measurement aid ------------------------------------------------------------------------------- */
 
 /* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;
- * Section 3.3: key norms, matching, similarity sets, merge + compaction). */
+ * Section 3.3: key norms, matching, similarity sets, merge + compaction).  For bf16 with d = 128 the key norms are
+ * written by score pass 2 and no norm kernel is launched: that slot then reads the cost of an empty event interval. */
 enum {
     LOOKM_K_SCORE_LSE = 0, LOOKM_K_SCORE_LSE_FOLD = 1,        /* pass 1 and the fold of its chunk partials */
     LOOKM_K_SCORE_COLSUM = 2, LOOKM_K_SCORE_COLSUM_FOLD = 3,  /* pass 2 and the fold of its chunk partials */
