@@ -44,16 +44,28 @@ __device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb,
             for (int r = 0; r < 16; ++r)
                 if (xb + 8 * (r >> 2) + (r & 3) > s) acc[r] = -INFINITY;   // key after the query
         }
-        float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
-#pragma unroll
-        for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
-        bm = fmaxf(bm, acc[15]);
-        const float mn = fmaxf(m, bm * scale2);
+        // The reference of the running sum is refreshed lazily: the block is first summed against the current
+        // reference m; only if that overflows (the first block of a row, where m is still "minus infinity", or a
+        // logit more than 64 binades above the reference) is the block maximum taken and the sum rescaled.  The
+        // result is the same up to rounding - a float sum keeps its relative precision at any magnitude below
+        // 2^64 - and the common case saves the maximum over the block.
         float sum = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
-        l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
-        m = mn;
+        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -m));
+        if (__builtin_expect(__any(!(sum <= 1.8e19f)), 0)) {     // also true for NaN; wave-uniform
+            float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+            for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
+            bm = fmaxf(bm, acc[15]);
+            const float mn = fmaxf(m, bm * scale2);
+            sum = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
+            l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
+            m = mn;
+        } else {
+            l += sum;
+        }
     } else {
         float sum = 0.f;
 #pragma unroll

@@ -51,6 +51,28 @@ def test_scores_large_logits_and_determinism():
     np.testing.assert_allclose(s.sum(1), 600, rtol=1e-5)
 
 
+def test_scores_logits_that_jump_late_in_the_row():
+    # pass 1 sums a block against the row's current reference and only takes a new maximum when that overflows:
+    # tiny keys first, then a few keys whose logits lie hundreds of binades higher (and lower), forces the refresh
+    # in the middle of rows, in interior and in diagonal tiles
+    H, L, d = 2, 900, 128
+    g = torch.Generator().manual_seed(12)
+    q = torch.randn(H, L, d, generator=g)
+    k = torch.randn(H, L, d, generator=g) * 0.02
+    for j in (130, 131, 400, 777, 899):
+        k[:, j] *= 1500.0                                   # logits of about +-300
+    q, k = q.to(torch.bfloat16), k.to(torch.bfloat16)
+    a = lookm.lookm_scores(q.cuda(), k.cuda())
+    assert torch.equal(a, lookm.lookm_scores(q.cuda(), k.cuda()))
+    s = a.cpu().numpy().astype(np.float64)
+    ref = oracle.scores(q, k)
+    assert np.all(np.isfinite(s))
+    big = ref > 1e-6
+    assert (np.abs(s - ref)[big] / ref[big]).max() < 1e-4
+    assert np.abs(s - ref)[~big].max() < 1e-9
+    np.testing.assert_allclose(s.sum(1), L, rtol=1e-5)
+
+
 def test_scores_zero_queries_closed_form():
     L = 1000
     q = torch.zeros(1, L, 128, dtype=torch.bfloat16)
