@@ -145,7 +145,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     }
     const int s0 = tile * BS;
     const int n_chunks_total = (L + CT - 1) / CT;
-    const int u = g * nS + tile;               // slot of this (chunk, strip) in the partial arrays [h][chunk][strip][256]
+    // slot of this (chunk, strip) in the partial arrays [h][chunk][strip][256]; pass 1 under an observation window
+    // only has the strips from the window's first one on, and indexes them from there
+    const int t_base = (PASS == 1) ? R0 / BS : 0, nSp = nS - t_base;
+    const int u = g * nSp + (tile - t_base);
     // h runs over the query heads; with grouped query heads, `group` consecutive ones read key head h / group
     const bf16_t* qh = q + (size_t)h * L * SD;
     const bf16_t* kh = k + (size_t)(h / group) * L * SD;
@@ -295,8 +298,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
     // chunk's partial for rows 0..255 of the strip
-    float* pa = part_a + ((size_t)h * n_chunks_total * nS + u) * BS;
-    float* pb = part_b + ((size_t)h * n_chunks_total * nS + u) * BS;
+    float* pa = part_a + ((size_t)h * n_chunks_total * nSp + u) * BS;
+    float* pb = part_b + ((size_t)h * n_chunks_total * nSp + u) * BS;
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const int r = wave * 64 + cb * 32 + n;
@@ -328,14 +331,17 @@ k_score_combine(int group, int L, int R0, int C, const float* __restrict__ part_
     const int CT = C * BX, nS = gridDim.x, G = (L + CT - 1) / CT;
     const int g0 = first_chunk(PASS, tile, CT, R0), nc = strip_chunks(PASS, tile, L, CT, R0);
     if (nc == 0) return;     // pass 1 under a window: a strip with no row that counts (its values are never read)
-    const size_t stride = (size_t)nS * BS;      // from one chunk of a strip to the next
+    const int t_base = (PASS == 1) ? R0 / BS : 0, nSp = nS - t_base;   // as in k_score_mfma
+    const size_t stride = (size_t)nSp * BS;     // from one chunk of a strip to the next
     const int h_first = (PASS == 1) ? h : h * group;      // first query head whose partials are read
-    const float* pa = part_a + (((size_t)h_first * G + g0) * nS + tile) * BS + r;
-    const float* pb = part_b + (((size_t)h_first * G + g0) * nS + tile) * BS + r;
+    const float* pa = part_a + (((size_t)h_first * G + g0) * nSp + (tile - t_base)) * BS + r;
+    const float* pb = part_b + (((size_t)h_first * G + g0) * nSp + (tile - t_base)) * BS + r;
     if (PASS == 1) {
         float M = -1e30f;
+#pragma unroll 8   // the loads do not depend on each other: eight in flight
         for (int c = 0; c < nc; ++c) M = fmaxf(M, pa[c * stride]);
         float Ls = 0.f;
+#pragma unroll 8
         for (int c = 0; c < nc; ++c) Ls = fmaf(pb[c * stride], exp2f(pa[c * stride] - M), Ls);
         out[(size_t)h * L + row] = M + log2f(Ls);
     } else {
@@ -394,9 +400,18 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
     const int group = H / kv_heads;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     const int C = chunk_tiles(H, L);
-    // the chunk length is the full problem's also under a window, so the partial arrays keep their layout and size
-    const int U1 = total_chunks(1, L, C, R0), U2 = total_chunks(2, L, C, R0);
     const int G = (L + C * lookm::BX - 1) / (C * lookm::BX);
+    // Pass 2 keeps the full problem's chunk length also under a window (its partial arrays keep their layout).
+    // Pass 1 under a window runs only the last strips, each over all keys: shorter chunks give the chip enough
+    // workgroups, as far as the partial arrays (sized for the full problem) hold them.
+    int C1 = C;
+    if (R0 > 0) {
+        const int nS1 = nS - R0 / lookm::BS;
+        const long want = (long)nS1 * ((L + lookm::BX - 1) / lookm::BX) * H / 2048;   // tiles per chunk for ~2048 units
+        C1 = (int)std::min<long>(C, std::max<long>(4, want));
+        while (C1 < C && (long)((L + C1 * lookm::BX - 1) / (C1 * lookm::BX)) * nS1 > (long)G * nS) ++C1;
+    }
+    const int U1 = total_chunks(1, L, C1, R0), U2 = total_chunks(2, L, C, R0);
     float* part_a = scratch;
     float* part_b = scratch + (size_t)H * G * nS * lookm::BS;
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
@@ -404,9 +419,9 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
     if (!lse_in) {
         hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, group, L, R0,
-                           scale2, C, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
+                           scale2, C1, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
         mark(LOOKM_K_SCORE_LSE);
-        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, 1, L, R0, C, part_a, part_b, lse);
+        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, 1, L, R0, C1, part_a, part_b, lse);
         mark(LOOKM_K_SCORE_LSE_FOLD);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
