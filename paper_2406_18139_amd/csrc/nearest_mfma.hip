@@ -61,7 +61,9 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     rnorm += (size_t)h * L;
     kept += (size_t)h * B;
     evicted += (size_t)h * Le;
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, n = lane & 31;
+    // the wave number goes through a scalar register, so that what derives from it stays scalar
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5,
+              n = lane & 31;
     const int w0 = strip * NBS + wave * 64;   // first evicted-list index of this wave
 
     nbf16x8 sf[2][8];
@@ -100,9 +102,13 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         ix3 = kept[min((x0) + ld_row + 48, B - 1)];            \
         if (tid < NBX) ridx = kept[min((x0) + tid, B - 1)];    \
     } while (0)
+    // a uniform base plus a 32-bit byte offset per lane (a position is below 2^15, a row 256 bytes); the 16 rows
+    // between two pieces do not change row & 7, so the swizzled chunk is the same for all four
+    const char* kb = reinterpret_cast<const char*>(k);
+    const uint32_t chunk_off = (uint32_t)((ld_chunk ^ (ld_row & 7)) * 16);
 #define LOOKM_ROW_TO_LDS(ix, j, buf)                                                                              \
     __builtin_amdgcn_global_load_lds(                                                                             \
-        (const __attribute__((address_space(1))) void*)(k + (size_t)(ix)*ND + ((ld_chunk ^ ((ld_row + 16 * (j)) & 7)) * 8)), \
+        (const __attribute__((address_space(1))) void*)(kb + ((uint32_t)(ix) * (ND * 2) + chunk_off)),            \
         (__attribute__((address_space(3))) void*)&xs[buf][((j)*4 + wave) * 4 * NXROW], 16, 0, 0)
 #define LOOKM_LOAD_TILE(buf)                                   \
     do {                                                       \
@@ -116,6 +122,10 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     do {                                                       \
         if (tid < NBX) xr[buf][tid] = stage_r;                 \
     } while (0)
+
+    // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks); scalars, not an array
+    const int fo0 = ((0 + half) ^ (n & 7)) * 8, fo1 = ((2 + half) ^ (n & 7)) * 8, fo2 = ((4 + half) ^ (n & 7)) * 8,
+              fo3 = ((6 + half) ^ (n & 7)) * 8;
 
     // per stationary row of this lane; the initial state decodes to slot 0 with t = 0 (= cosine -1)
     int bhi[2] = {0, 0};            // best truncated key (>> 4)
@@ -139,8 +149,11 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             nbf16x8 a[8];
             const bf16_t* ap = &xs[buf][(rb * 32 + n) * NXROW];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                a[ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + (((2 * ks + half) ^ (n & 7)) * 8)));
+            for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
+                const int fo = (ks == 0) ? fo0 : (ks == 1) ? fo1 : (ks == 2) ? fo2 : fo3;
+                a[ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + fo));
+                a[ks + 4] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(ap + fo + 64));
+            }
             nf32x16 acc[2];
 #pragma unroll
             for (int r = 0; r < 16; ++r) { acc[0][r] = 0.f; acc[1][r] = 0.f; }

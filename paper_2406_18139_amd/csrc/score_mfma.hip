@@ -156,7 +156,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     const bf16_t* X = (PASS == 1) ? kh : qh;   // streamed tensor
     const float* lse_h = lse2 + (size_t)h * L;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5, n = lane & 31;
+    // the wave number is uniform across a wave: taken through a scalar register, everything derived from it (the
+    // wave's first row, loop bounds, LDS addresses) stays in scalar registers and scalar branches
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5,
+              n = lane & 31;
     const int w0 = s0 + wave * 64;
 
     // stationary fragments: lane holds row (w0 + cb*32 + n), dims ks*16 + half*8 .. +7
@@ -185,15 +188,28 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     constexpr int NLD = BX / 16;   // 1 KB pieces per wave and tile
     const int ld_sub = lane >> 4, ld_pos = lane & 15;
     float stage_l = 0.f;
+    // byte offset of this lane's 16 bytes inside a tile: row (wave*4 + ld_sub) of the first 1 KB piece, swizzled chunk
+    // (the 16 rows between two pieces do not change row & 7)
+    const uint32_t lane_off = (uint32_t)((wave * 4 + ld_sub) * (SD * 2) + ((ld_pos ^ ((wave * 4 + ld_sub) & 7)) * 16));
+    const char* Xb = reinterpret_cast<const char*>(X);
     auto load_tile = [&](int x0, int buf) {
+        if (x0 + BX <= L) {          // scalar test: a whole tile inside the tensor needs no clamping
+            const uint32_t o = (uint32_t)x0 * (SD * 2) + lane_off;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            const int row = (i * 4 + wave) * 4 + ld_sub;                        // row inside the tile
-            const int grow = min(x0 + row, L - 1);
-            const bf16_t* src = X + (size_t)grow * SD + ((ld_pos ^ (row & 7)) * 8);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW],
-                                             16, 0, 0);
+            for (int i = 0; i < NLD; ++i)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void*)(Xb + (o + (uint32_t)i * 16 * SD * 2)),
+                    (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW], 16, 0, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) {
+                const int row = (i * 4 + wave) * 4 + ld_sub;                        // row inside the tile
+                const int grow = min(x0 + row, L - 1);
+                const bf16_t* src = X + (size_t)grow * SD + ((ld_pos ^ (row & 7)) * 8);
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                                 (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW],
+                                                 16, 0, 0);
+            }
         }
         if (PASS == 2 && tid < BX)   // negated at store time; rows outside [R0, L) get +inf and contribute nothing
             stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
@@ -243,6 +259,11 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
+    // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks)
+    int frag_off[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) frag_off[ks] = ((2 * ks + half) ^ (n & 7)) * 8;
+
     // One tile.  MASK = true evaluates the causal condition per element and is correct for every tile;
     // MASK = false is the same minus the comparisons, for tiles known to lie entirely inside the causal
     // region.  Each variant gets a loop of its own below (one code path per loop).
@@ -259,8 +280,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                 const bf16_t* ap = &xs[buf][(rb * 32 + n) * XROW];
                 bf16x8 a[8];
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks)
-                    a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + (((2 * ks + half) ^ (n & 7)) * 8)));
+                for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
+                    a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
+                    a[ks + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
+                }
                 f32x16 Xc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
                 f32x16 Yc = Xc;
 #pragma unroll
