@@ -20,6 +20,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <type_traits>
 
 namespace lookm {
 
@@ -39,8 +40,14 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                const int32_t* __restrict__ evicted, int H, int L, int B, int Le, int n_strips, int n_chunks, int CT,
                NearestPartial* __restrict__ part)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xs[2][NBX * NXROW];
-    __shared__ __attribute__((aligned(16))) float xr[2][NBX];
+    // Two tiles as separate arrays, and a tile loop unrolled by two with the buffer known at compile time: the
+    // compiler then sees that a fragment read of one array cannot alias the loads in flight to the other and
+    // does not wait for them (with one array indexed by a run-time buffer number it waits for every outstanding
+    // load before the first LDS read of a tile, which serialises the prefetch with the MFMA block of the same wave).
+    __shared__ __attribute__((aligned(16))) bf16_t xs0[NBX * NXROW];
+    __shared__ __attribute__((aligned(16))) bf16_t xs1[NBX * NXROW];
+    __shared__ __attribute__((aligned(16))) float xr0[NBX];
+    __shared__ __attribute__((aligned(16))) float xr1[NBX];
 
     // XCD-affine enumeration (see k_score_mfma): units of a head are chunk-major
     const int U = n_strips * n_chunks;
@@ -66,22 +73,11 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
               n = lane & 31;
     const int w0 = strip * NBS + wave * 64;   // first evicted-list index of this wave
 
-    nbf16x8 sf[2][8];
-    float off[2];    // ||k_e|| of this lane's two evicted keys (0 for a zero key)
-#pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int ev = w0 + cb * 32 + n;
-        const bf16_t* row = (ev < Le) ? k + (size_t)evicted[ev] * ND : nullptr;
-        const float rne = (ev < Le) ? rnorm[evicted[ev]] : 0.f;
-        off[cb] = (rne > 0.f) ? 1.0f / rne : 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row) v = *reinterpret_cast<const uint4*>(row + ks * 16 + half * 8);
-            sf[cb][ks] = __builtin_bit_cast(nbf16x8, v);
-        }
-    }
-
+    // Evicted keys of this lane: positions first (list entries past the end of the list repeat its last entry; their
+    // results land in partial slots that nothing reads), so that every load below is unconditional and the
+    // prologue is two round trips to memory - positions, then rows - instead of one per branch.
+    const int ev0 = min(w0 + n, Le - 1), ev1 = min(w0 + 32 + n, Le - 1);
+    const int pos0 = evicted[ev0], pos1 = evicted[ev1];
     const int x_begin = chunk * CT, x_end = min(B, x_begin + CT);
     const int n_it = (x_end - x_begin + NBX - 1) / NBX;
     const int ld_row = tid >> 4, ld_chunk = tid & 15;
@@ -106,21 +102,27 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     // between two pieces do not change row & 7, so the swizzled chunk is the same for all four
     const char* kb = reinterpret_cast<const char*>(k);
     const uint32_t chunk_off = (uint32_t)((ld_chunk ^ (ld_row & 7)) * 16);
-#define LOOKM_ROW_TO_LDS(ix, j, buf)                                                                              \
-    __builtin_amdgcn_global_load_lds(                                                                             \
-        (const __attribute__((address_space(1))) void*)(kb + ((uint32_t)(ix) * (ND * 2) + chunk_off)),            \
-        (__attribute__((address_space(3))) void*)&xs[buf][((j)*4 + wave) * 4 * NXROW], 16, 0, 0)
-#define LOOKM_LOAD_TILE(buf)                                   \
-    do {                                                       \
-        LOOKM_ROW_TO_LDS(ix0, 0, buf);                         \
-        LOOKM_ROW_TO_LDS(ix1, 1, buf);                         \
-        LOOKM_ROW_TO_LDS(ix2, 2, buf);                         \
-        LOOKM_ROW_TO_LDS(ix3, 3, buf);                         \
-        if (tid < NBX) stage_r = rnorm[ridx];                  \
+#define LOOKM_ROW_TO_LDS(o, j, buf)                                                                               \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kb + (o)),                   \
+                                     (__attribute__((address_space(3))) void*)&(buf)[((j)*4 + wave) * 4 * NXROW], 16,   \
+                                     0, 0)
+    // All four offsets are formed before the first load to LDS is issued (the empty asm keeps them together): once a
+    // load to LDS is in flight next to ordinary loads the compiler waits for everything outstanding, which in the
+    // prologue would be the 16 row loads of the stationary keys.
+#define LOOKM_LOAD_TILE(buf)                                                                  \
+    do {                                                                                      \
+        const uint32_t o0 = (uint32_t)ix0 * (ND * 2) + chunk_off, o1 = (uint32_t)ix1 * (ND * 2) + chunk_off, \
+                       o2 = (uint32_t)ix2 * (ND * 2) + chunk_off, o3 = (uint32_t)ix3 * (ND * 2) + chunk_off; \
+        asm volatile("" ::"v"(o0), "v"(o1), "v"(o2), "v"(o3), "v"(ridx));                     \
+        LOOKM_ROW_TO_LDS(o0, 0, buf);                                                         \
+        LOOKM_ROW_TO_LDS(o1, 1, buf);                                                         \
+        LOOKM_ROW_TO_LDS(o2, 2, buf);                                                         \
+        LOOKM_ROW_TO_LDS(o3, 3, buf);                                                         \
+        if (tid < NBX) stage_r = rnorm[ridx];                                                 \
     } while (0)
-#define LOOKM_STORE_TILE(buf)                                  \
+#define LOOKM_STORE_TILE(rbuf)                                 \
     do {                                                       \
-        if (tid < NBX) xr[buf][tid] = stage_r;                 \
+        if (tid < NBX) (rbuf)[tid] = stage_r;                  \
     } while (0)
 
     // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks); scalars, not an array
@@ -132,22 +134,42 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     int bkey[2] = {15, 15};         // its full key (low 4 bits: 15 - entry number)
     int bxb[2] = {0, 0};            // slot of entry 0 of the block it came from
 
-    LOOKM_LOAD_INDEX(x_begin);
-    LOOKM_LOAD_TILE(0);
+    LOOKM_LOAD_INDEX(x_begin);           // in flight together with the evicted positions
+
+    nbf16x8 sf[2][8];
+    float off[2];    // ||k_e|| of this lane's two evicted keys (0 for a zero key)
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+        const int pos = cb ? pos1 : pos0;
+        const bf16_t* row = k + (size_t)pos * ND;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+            sf[cb][ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(row + ks * 16 + half * 8));
+    }
+    const float rne0 = rnorm[pos0], rne1 = rnorm[pos1];
+    LOOKM_LOAD_TILE(xs0);
     LOOKM_LOAD_INDEX(x_begin + NBX);     // clamped, so always in range
-    LOOKM_STORE_TILE(0);
+    LOOKM_STORE_TILE(xr0);
+    off[0] = (rne0 > 0.f) ? 1.0f / rne0 : 0.f;
+    off[1] = (rne1 > 0.f) ? 1.0f / rne1 : 0.f;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
-    for (int it = 0; it < n_it; ++it) {
-        const int buf = it & 1, x0 = x_begin + it * NBX;
+
+    auto tile_step = [&](auto buf_tag, int it) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        bf16_t* cur = BUF ? xs1 : xs0;
+        bf16_t* nxt = BUF ? xs0 : xs1;
+        float* cur_r = BUF ? xr1 : xr0;
+        float* nxt_r = BUF ? xr0 : xr1;
+        const int x0 = x_begin + it * NBX;
         if (it + 1 < n_it) {
-            LOOKM_LOAD_TILE(buf ^ 1);            // rows of tile it+1 (positions fetched one iteration ago)
+            LOOKM_LOAD_TILE(nxt);                // rows of tile it+1 (positions fetched one iteration ago)
             LOOKM_LOAD_INDEX(x0 + 2 * NBX);      // positions of tile it+2
         }
 #pragma unroll 1
         for (int rb = 0; rb < 2; ++rb) {
             nbf16x8 a[8];
-            const bf16_t* ap = &xs[buf][(rb * 32 + n) * NXROW];
+            const bf16_t* ap = &cur[(rb * 32 + n) * NXROW];
 #pragma unroll
             for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
                 const int fo = (ks == 0) ? fo0 : (ks == 1) ? fo1 : (ks == 2) ? fo2 : fo3;
@@ -163,7 +185,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], acc[1], 0, 0, 0);
             }
             const int xb = x0 + rb * 32 + 4 * half;   // slot of entry r: xb + 8*(r/4) + r%4
-            const float* rp = &xr[buf][rb * 32 + 4 * half];
+            const float* rp = &cur_r[rb * 32 + 4 * half];
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
                 int u[16];
@@ -190,9 +212,13 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 bxb[cb] = better ? xb : bxb[cb];
             }
         }
-        if (it + 1 < n_it) LOOKM_STORE_TILE(buf ^ 1);
+        if (it + 1 < n_it) LOOKM_STORE_TILE(nxt_r);
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the next tile's direct-to-LDS loads have landed
         __syncthreads();
+    };
+    for (int it = 0; it < n_it; it += 2) {
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < n_it) tile_step(std::integral_constant<int, 1>{}, it + 1);
     }
 #undef LOOKM_ROW_TO_LDS
 #undef LOOKM_LOAD_INDEX

@@ -118,8 +118,14 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
              int C, int U, const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a,
              float* __restrict__ part_b, float* __restrict__ rnorm)
 {
-    __shared__ __attribute__((aligned(16))) bf16_t xs[2][BX * XROW];
-    __shared__ __attribute__((aligned(16))) float xl[2][BX];   // pass 2: -lse2[i] of the streamed query rows
+    // Two tiles as separate arrays, with the buffer of a tile known at compile time (the tile loop is unrolled by
+    // two): the compiler then sees that a fragment read of one array cannot alias the loads in flight to the
+    // other.  With one array indexed by a run-time buffer number it waits for every outstanding load before a
+    // tile's first LDS read, which serialises the prefetch with the MFMA block of the same wave.
+    __shared__ __attribute__((aligned(16))) bf16_t xs0[BX * XROW];
+    __shared__ __attribute__((aligned(16))) bf16_t xs1[BX * XROW];
+    __shared__ __attribute__((aligned(16))) float xl0[BX];   // pass 2: -lse2[i] of the streamed query rows
+    __shared__ __attribute__((aligned(16))) float xl1[BX];
 
     // Consecutive workgroup ids go to consecutive XCDs.  With 8 or more heads, XCD x works through heads
     // x, x+8, ... one at a time, so its L2 holds one head's current chunk; with fewer heads each head
@@ -192,14 +198,14 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     // (the 16 rows between two pieces do not change row & 7)
     const uint32_t lane_off = (uint32_t)((wave * 4 + ld_sub) * (SD * 2) + ((ld_pos ^ ((wave * 4 + ld_sub) & 7)) * 16));
     const char* Xb = reinterpret_cast<const char*>(X);
-    auto load_tile = [&](int x0, int buf) {
+    auto load_tile = [&](int x0, bf16_t* xsb) {
         if (x0 + BX <= L) {          // scalar test: a whole tile inside the tensor needs no clamping
             const uint32_t o = (uint32_t)x0 * (SD * 2) + lane_off;
 #pragma unroll
             for (int i = 0; i < NLD; ++i)
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(Xb + (o + (uint32_t)i * 16 * SD * 2)),
-                    (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW], 16, 0, 0);
+                    (__attribute__((address_space(3))) void*)&xsb[(i * 4 + wave) * 4 * XROW], 16, 0, 0);
         } else {
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
@@ -207,23 +213,23 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                 const int grow = min(x0 + row, L - 1);
                 const bf16_t* src = X + (size_t)grow * SD + ((ld_pos ^ (row & 7)) * 8);
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                                 (__attribute__((address_space(3))) void*)&xs[buf][(i * 4 + wave) * 4 * XROW],
+                                                 (__attribute__((address_space(3))) void*)&xsb[(i * 4 + wave) * 4 * XROW],
                                                  16, 0, 0);
             }
         }
         if (PASS == 2 && tid < BX)   // negated at store time; rows outside [R0, L) get +inf and contribute nothing
             stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
     };
-    auto store_tile = [&](int buf) {
-        if (PASS == 2 && tid < BX) xl[buf][tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
+    auto store_tile = [&](float* xlb) {
+        if (PASS == 2 && tid < BX) xlb[tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
     float run[2] = {0.f, 0.f};                          // pass 2 state
     const int sA = w0 + n, sB = w0 + 32 + n;            // stationary index of this lane for cb = 0, 1
 
-    load_tile(x_begin, 0);
-    store_tile(0);
+    load_tile(x_begin, xs0);
+    store_tile(xl0);
     if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0) && h % group == 0) {
         // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
         // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
@@ -267,17 +273,21 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     // One tile.  MASK = true evaluates the causal condition per element and is correct for every tile;
     // MASK = false is the same minus the comparisons, for tiles known to lie entirely inside the causal
     // region.  Each variant gets a loop of its own below (one code path per loop).
-    auto tile_step = [&](auto mask_tag, int it) {
+    auto tile_step = [&](auto mask_tag, auto buf_tag, int it) {
         constexpr bool MASK = decltype(mask_tag)::value;
-        const int buf = it & 1;
+        constexpr int BUF = decltype(buf_tag)::value;
+        bf16_t* cur = BUF ? xs1 : xs0;
+        bf16_t* nxt = BUF ? xs0 : xs1;
+        float* cur_l = BUF ? xl1 : xl0;
+        float* nxt_l = BUF ? xl0 : xl1;
         const int x0 = x_begin + it * BX;
-        if (it + 1 < n_it) load_tile(x0 + BX, buf ^ 1);
+        if (it + 1 < n_it) load_tile(x0 + BX, nxt);
         // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
         const bool skip = MASK && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
         if (!skip) {
 #pragma unroll 1   // one block of 32 streamed rows at a time keeps the kernel within 168 VGPRs
             for (int rb = 0; rb < BX / 32; ++rb) {
-                const bf16_t* ap = &xs[buf][(rb * 32 + n) * XROW];
+                const bf16_t* ap = &cur[(rb * 32 + n) * XROW];
                 bf16x8 a[8];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
@@ -292,31 +302,39 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                     Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
                 }
                 const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
-                const float* nl = &xl[buf][rb * 32 + 4 * half];
+                const float* nl = &cur_l[rb * 32 + 4 * half];
                 block_epilogue<PASS, MASK>(Xc, scale2, xb, sA, nl, m[0], l[0], run[0]);
                 block_epilogue<PASS, MASK>(Yc, scale2, xb, sB, nl, m[1], l[1], run[1]);
             }
         }
-        if (it + 1 < n_it) store_tile(buf ^ 1);
+        if (it + 1 < n_it) store_tile(nxt_l);
         __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the next tile's direct-to-LDS loads have landed
         __syncthreads();
     };
     using masked = std::integral_constant<bool, true>;
     using plain = std::integral_constant<bool, false>;
 
+    // Which tiles need the mask (wave-uniform, so the choice is a scalar branch):
+    //   pass 1, keys stream upwards: tiles with x0 + BX - 1 <= w0 hold only keys at or before every query row of
+    //   this wave, the tiles after them touch the diagonal;
+    //   pass 2, query rows stream upwards from the diagonal: tiles with x0 >= w0 + 63 need no mask.
+    int plain_from, plain_to;
     if (PASS == 1) {
-        // keys stream upwards: tiles with x0 + BX - 1 <= w0 hold only keys at or before every query row
-        // of this wave; the tiles after them touch the diagonal
-        int n_plain = (w0 - x_begin + 1) / BX;        // largest count with x_begin + BX*count - 1 <= w0
-        n_plain = max(0, min(n_plain, n_it));
-        for (int it = 0; it < n_plain; ++it) tile_step(plain{}, it);
-        for (int it = n_plain; it < n_it; ++it) tile_step(masked{}, it);
+        const int n_plain = (w0 - x_begin + 1) / BX;        // largest count with x_begin + BX*count - 1 <= w0
+        plain_from = 0;
+        plain_to = max(0, min(n_plain, n_it));
     } else {
-        // query rows stream upwards from the diagonal: tiles with x0 >= w0 + 63 need no mask
-        int n_masked = (w0 + 63 - x_begin + BX - 1) / BX;
-        n_masked = max(0, min(n_masked, n_it));
-        for (int it = 0; it < n_masked; ++it) tile_step(masked{}, it);
-        for (int it = n_masked; it < n_it; ++it) tile_step(plain{}, it);
+        const int n_masked = (w0 + 63 - x_begin + BX - 1) / BX;
+        plain_from = max(0, min(n_masked, n_it));
+        plain_to = n_it;
+    }
+    auto one_tile = [&](auto buf_tag, int it) {
+        if (it >= plain_from && it < plain_to) tile_step(plain{}, buf_tag, it);
+        else tile_step(masked{}, buf_tag, it);
+    };
+    for (int it = 0; it < n_it; it += 2) {
+        one_tile(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < n_it) one_tile(std::integral_constant<int, 1>{}, it + 1);
     }
 
     // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
