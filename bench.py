@@ -155,6 +155,9 @@ def main() -> int:
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
     ap.add_argument("--score-window", type=int, default=0,
                     help="variant: scores from the last W query rows only (lookm_scores_window), via a lookm_job")
+    ap.add_argument("--probe-mfma", action="store_true",
+                    help="only measure the sustained rate of the bf16 MFMA instruction from registers (constant and "
+                         "random operands, 1-3 waves per SIMD) and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy kernel (to scale HBM byte counters) and exit")
     args = ap.parse_args()
@@ -180,6 +183,16 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
         print(json.dumps({"calibration": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n, "copies": 3}))
+        return 0
+
+    if args.probe_mfma:
+        res = {}
+        for rnd in (False, True):
+            for wps in (1, 2, 3):
+                res[f"{'random' if rnd else 'constant'}_operands_{wps}_waves_per_simd"] = round(
+                    lookm.lookm_probe_mfma(rnd, wps, iters=2048 * 3 // wps, reps=20), 1)
+        print(json.dumps({"probe": "v_mfma_f32_32x32x16_bf16 from registers, 16 per block in two accumulator chains",
+                          "unit": "TFLOP/s", "datasheet_peak": PEAK_MFMA_BF16 / 1e12, "sustained": res}))
         return 0
 
     if args.workload == "stack":
@@ -287,6 +300,15 @@ def main() -> int:
                         "kind": "oracle", "seconds": round(sec, 2),
                         "sample": f"heads 0..{n_heads - 1} of {w.H} of the same layer (one head per thread), "
                                   f"scaled by {w.H}/{n_heads} to the whole layer"}
+
+    # context for the MFMA-bound rooflines: what the matrix cores of this GPU sustain on the same instruction with
+    # operands that change every instruction, from registers alone (measured after the timed region)
+    mfma_sustained = None
+    if w.dtype == "bf16":
+        mfma_sustained = round(lookm.lookm_probe_mfma(True, 3, iters=2048, reps=20), 1)
+        roofline["sustained_mfma_probe"] = {"value": mfma_sustained, "unit": "TFLOP/s",
+                                            "what": "v_mfma_f32_32x32x16_bf16 from registers, random operands, "
+                                                    "3 waves per SIMD (lookm_probe_mfma)"}
 
     metric = "prompt KV tokens compressed/sec per layer (12K ctx)"
     if args.reuse_lse:

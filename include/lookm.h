@@ -302,6 +302,23 @@ int lookm_compress_profile(const void* q, const void* k, const void* v, const ui
 /* The same for any job (selection rule, observation window, supplied row log-sum-exp). */
 int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, void* hip_stream);
 
+/*
+ * Measurement aid, no part of the method (for callers that want the realistic ceiling of the MFMA-bound kernels
+ * next to the datasheet peak): the rate at which this GPU sustains v_mfma_f32_32x32x16_bf16, the instruction the
+ * score and matching kernels are built on, from registers alone - 8 A and 16 B fragments per wave, blocks of 16
+ * MFMAs in two accumulator chains, no memory traffic.
+ *   random_operands  0: every operand element is 1.0;  1: pseudo-random bf16 values of magnitude [0.25, 4) that differ
+ *                    from instruction to instruction, as real queries and keys do (the chip sustains less then)
+ *   waves_per_simd   1..3: the grid is (compute units x waves_per_simd) workgroups of 256 threads
+ *   iters            1..2^20 blocks of 16 MFMAs per wave and launch;  reps  1..1000 launches, the first half untimed
+ *   tflops_host      host, one float: 2*32*32*16 flop per MFMA over the time of the timed launches, in TFLOP/s
+ *   workspace        device, at least compute units x waves_per_simd x 1024 bytes (1 MiB always suffices), written
+ * Like the profile calls it SYNCHRONISES the stream and creates / destroys two HIP events.  Errors: INVALID_ARG
+ * for a null pointer or a count outside the ranges above, WORKSPACE for a workspace that is too small, DEVICE.
+ */
+int lookm_probe_mfma(int random_operands, int waves_per_simd, int iters, int reps, float* tflops_host,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,7 @@ OBJ = PKG / "_build"
 LIB = PKG / "liblookm.so"
 
 SOURCES = ["api.hip", "score_generic.hip", "score_mfma.hip", "select.hip", "nearest_generic.hip", "nearest_mfma.hip",
-           "merge.hip", "decode.hip"]
+           "merge.hip", "decode.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]

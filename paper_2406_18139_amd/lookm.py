@@ -33,7 +33,7 @@ EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "loo
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
            "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile", "lookm_decode_workspace_bytes",
-           "lookm_decode_attention", "lookm_scores_grouped"]
+           "lookm_decode_attention", "lookm_scores_grouped", "lookm_probe_mfma"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -109,6 +109,8 @@ def lib() -> ctypes.CDLL:
         L.lookm_job_profile.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(ctypes.c_float), vp]
         L.lookm_compress_batch.restype = I
         L.lookm_compress_batch.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(I), vp]
+        L.lookm_probe_mfma.restype = I
+        L.lookm_probe_mfma.argtypes = [I, I, I, I, ctypes.POINTER(ctypes.c_float), vp, sz, vp]
         _lib = L
     return _lib
 
@@ -318,6 +320,21 @@ def lookm_decode_attention(q, k_cache, v_cache, S: Optional[int] = None, out: Op
     if rc != OK:
         raise LookmError(rc, "lookm_decode_attention")
     return out
+
+
+def lookm_probe_mfma(random_operands: bool, waves_per_simd: int = 3, iters: int = 4096, reps: int = 20,
+                     workspace: Optional[torch.Tensor] = None) -> float:
+    """lookm_probe_mfma: sustained TFLOP/s of v_mfma_f32_32x32x16_bf16 from registers alone (a measurement aid).
+    Synchronises the current stream."""
+    if workspace is None:
+        workspace = torch.empty((1 << 20) + 256, dtype=torch.uint8, device="cuda")
+    wp, wn = _ws_ptr(workspace)
+    out = ctypes.c_float(0.0)
+    rc = lib().lookm_probe_mfma(int(bool(random_operands)), int(waves_per_simd), int(iters), int(reps),
+                                ctypes.byref(out), wp, wn, _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_probe_mfma")
+    return float(out.value)
 
 
 def lookm_job_profile(job: Job, reps: int) -> dict:

@@ -164,6 +164,19 @@ def test_decode_rejects_bad_arguments():
     assert call(wsn=16) == lookm.ERR_WORKSPACE and call(ws=None) == lookm.ERR_WORKSPACE
 
 
+def test_probe_rejects_bad_arguments():
+    import ctypes
+    L = lookm.lib()
+    out = ctypes.c_float(0.0)
+    def call(rnd=1, wps=3, iters=16, reps=2, o=ctypes.byref(out), ws=FAKE, wsn=1 << 20):
+        return L.lookm_probe_mfma(rnd, wps, iters, reps, o, ws, wsn, None)
+
+    assert call(o=None) == lookm.ERR_INVALID_ARG and call(ws=None) == lookm.ERR_INVALID_ARG
+    assert call(wps=0) == lookm.ERR_INVALID_ARG and call(wps=4) == lookm.ERR_INVALID_ARG
+    assert call(iters=0) == lookm.ERR_INVALID_ARG and call(iters=(1 << 20) + 1) == lookm.ERR_INVALID_ARG
+    assert call(reps=0) == lookm.ERR_INVALID_ARG and call(reps=1001) == lookm.ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     t = torch.zeros(1, 8, 8)

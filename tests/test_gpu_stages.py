@@ -323,3 +323,10 @@ def test_merge_everything_into_one_slot():
     parity.check_merge(k[0].float().numpy(), kept, ev, assign[0], sim[0], "averaged", ko[0].float().cpu().numpy(),
                        torch.bfloat16)
     assert torch.equal(ko, vo)
+
+
+def test_mfma_probe_reports_a_plausible_rate():
+    """The measurement aid runs, and the rate it reports lies between a tenth of the datasheet peak and the peak."""
+    for rnd in (False, True):
+        t = lookm.lookm_probe_mfma(rnd, 3, iters=256, reps=6)
+        assert 250.0 < t < 2600.0, (rnd, t)
