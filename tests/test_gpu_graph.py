@@ -1,0 +1,79 @@
+"""The library enqueues kernels only - no allocation, no memset, no synchronisation on the compression and decode
+paths - so a caller can capture them into a HIP graph.  Captured once and replayed several times with eager work and
+synchronisations in between, every replay has to reproduce the eager results bit for bit."""
+import pytest
+import torch
+
+from paper_2406_18139_amd import lookm
+from paper_2406_18139_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+def _eager_noise(dev):
+    # unrelated eager work between replays: touches the allocator and the default stream
+    x = torch.randn(1 << 16, device=dev)
+    (x * 2 + 1).sum().item()
+
+
+def test_compress_replays_in_a_hip_graph():
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w)
+    dev = torch.device("cuda:0")
+    qg, kg, vg, mg = (t.to(dev) for t in (q, k, v, mask))
+    B, M, mode = w.budget(), w.M, w.modes[0]
+    dt = lookm.BF16 if w.dtype == "bf16" else lookm.F32
+    ref = lookm.lookm_compress(qg, kg, vg, mg, B, M, mode)
+    out = lookm.alloc_outputs(w.H, w.L, w.d, B, qg.dtype, dev)
+    ws = lookm.alloc_workspace(w.H, w.L, w.d, B, dt, dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                      # one warm-up call on the capture stream, as torch asks
+        lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
+    for rep in range(4):
+        out.k_out.zero_(); out.v_out.zero_(); out.kept_idx.zero_(); out.status.fill_(-99)
+        _eager_noise(dev)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(out.status.item()) == 0, rep
+        assert torch.equal(out.kept_idx, ref.kept_idx), rep
+        assert torch.equal(out.k_out, ref.k_out) and torch.equal(out.v_out, ref.v_out), rep
+        _eager_noise(dev)
+
+
+def test_decode_replays_in_a_hip_graph():
+    dev = torch.device("cuda:0")
+    H, S, d = 32, 2276, 128
+    g = torch.Generator(device=dev).manual_seed(11)
+    q = torch.randn((H, d), generator=g, device=dev).to(torch.bfloat16)
+    k = torch.randn((H, S, d), generator=g, device=dev).to(torch.bfloat16)
+    v = torch.randn((H, S, d), generator=g, device=dev).to(torch.bfloat16)
+    ref = lookm.lookm_decode_attention(q, k, v)
+    out = torch.empty_like(ref)
+    ws = torch.empty(int(lookm.lib().lookm_decode_workspace_bytes(H, d)) + 256, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lookm.lookm_decode_attention(q, k, v, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lookm.lookm_decode_attention(q, k, v, out=out, workspace=ws)
+    for rep in range(4):
+        out.zero_()
+        _eager_noise(dev)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, ref), rep
+    # new inputs in the same buffers: the graph reads them at replay time
+    q.copy_(torch.randn((H, d), generator=g, device=dev).to(torch.bfloat16))
+    ref2 = lookm.lookm_decode_attention(q, k, v)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, ref2)
