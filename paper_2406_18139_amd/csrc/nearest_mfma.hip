@@ -28,6 +28,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 nbf16x8;
 typedef __attribute__((ext_vector_type(16))) float nf32x16;
 
 constexpr int ND = 128, NBS = 256, NBX = 64, NXROW = 128;   // LDS rows are unpadded, chunks swizzled
+static_assert(NBX == 64, "the norms of a tile are staged by wave 0, one row per lane");
 
 // partial result of one (evicted strip, chunk): key = float bits of t >> 4, slot
 struct NearestPartial {
@@ -96,7 +97,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         ix1 = kept[min((x0) + ld_row + 16, B - 1)];            \
         ix2 = kept[min((x0) + ld_row + 32, B - 1)];            \
         ix3 = kept[min((x0) + ld_row + 48, B - 1)];            \
-        if (tid < NBX) ridx = kept[min((x0) + tid, B - 1)];    \
+        if (wave == 0) ridx = kept[min((x0) + tid, B - 1)];    \
     } while (0)
     // a uniform base plus a 32-bit byte offset per lane (a position is below 2^15, a row 256 bytes); the 16 rows
     // between two pieces do not change row & 7, so the swizzled chunk is the same for all four
@@ -118,11 +119,11 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         LOOKM_ROW_TO_LDS(o1, 1, buf);                                                         \
         LOOKM_ROW_TO_LDS(o2, 2, buf);                                                         \
         LOOKM_ROW_TO_LDS(o3, 3, buf);                                                         \
-        if (tid < NBX) stage_r = rnorm[ridx];                                                 \
+        if (wave == 0) stage_r = rnorm[ridx];                                                 \
     } while (0)
 #define LOOKM_STORE_TILE(rbuf)                                 \
     do {                                                       \
-        if (tid < NBX) (rbuf)[tid] = stage_r;                  \
+        if (wave == 0) (rbuf)[tid] = stage_r;                  \
     } while (0)
 
     // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks); scalars, not an array

@@ -24,6 +24,7 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int SD = 128;        // head dim
 constexpr int BS = 256;        // stationary rows per workgroup
 constexpr int BX = 64;         // streamed rows per iteration
+static_assert(BX == 64, "the lse staging of pass 2 is done by wave 0, one row per lane");
 constexpr int XROW = 128;       // LDS row = 256 B, unpadded; the 16-byte chunk c of row r sits at chunk c ^ (r & 7),
                                // so 16-byte reads of 8 consecutive rows at the same c hit all 32 banks once
 
@@ -39,33 +40,7 @@ __device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb,
                                                float& m, float& l, float& run)
 {
     if (PASS == 1) {
-        if (MASK) {
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (xb + 8 * (r >> 2) + (r & 3) > s) acc[r] = -INFINITY;   // key after the query
-        }
-        // The reference of the running sum is refreshed lazily: the block is first summed against the current
-        // reference m; only if that overflows (the first block of a row, where m is still "minus infinity", or a
-        // logit more than 64 binades above the reference) is the block maximum taken and the sum rescaled.  The
-        // result is the same up to rounding - a float sum keeps its relative precision at any magnitude below
-        // 2^64 - and the common case saves the maximum over the block.
-        float sum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -m));
-        if (__builtin_expect(__any(!(sum <= 1.8e19f)), 0)) {     // also true for NaN; wave-uniform
-            float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
-#pragma unroll
-            for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
-            bm = fmaxf(bm, acc[15]);
-            const float mn = fmaxf(m, bm * scale2);
-            sum = 0.f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
-            l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
-            m = mn;
-        } else {
-            l += sum;
-        }
+        // handled by lse_pair_epilogue, two blocks at a time
     } else {
         float sum = 0.f;
 #pragma unroll
@@ -80,6 +55,55 @@ __device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb,
             }
         }
         run += sum;
+    }
+}
+
+// Pass 1, the two finished blocks of a wave (same 32 streamed keys against its two sets of 32 query rows).
+// The reference of a running sum is refreshed lazily: a block is first summed against the row's current reference m;
+// only if a sum overflows (the first block of a row, where m is still "minus infinity", or a logit more than 64
+// binades above the reference) is the block maximum taken and the running sum rescaled.  The result is the same up
+// to rounding - a float sum keeps its relative precision at any magnitude below 2^64 - and the common case saves
+// the maximum over the block.  One wave-uniform test covers both blocks (a branch on a vector result drains the
+// wave's vector pipeline, so there is one per pair, not one per block); the refresh is valid for a block that did
+// not overflow as well.
+__device__ __forceinline__ void lse_refresh(const f32x16& acc, float scale2, float& m, float& l)
+{
+    float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
+    bm = fmaxf(bm, acc[15]);
+    const float mn = fmaxf(m, bm * scale2);
+    float sum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
+    l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
+    m = mn;
+}
+
+template <bool MASK>
+__device__ __forceinline__ void lse_pair_epilogue(f32x16 X, f32x16 Y, float scale2, int xb, int sA, int sB,
+                                                  float (&m)[2], float (&l)[2])
+{
+    if (MASK) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int key = xb + 8 * (r >> 2) + (r & 3);
+            if (key > sA) X[r] = -INFINITY;   // key after the query
+            if (key > sB) Y[r] = -INFINITY;
+        }
+    }
+    float sx = 0.f, sy = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        sx += __builtin_amdgcn_exp2f(fmaf(X[r], scale2, -m[0]));
+        sy += __builtin_amdgcn_exp2f(fmaf(Y[r], scale2, -m[1]));
+    }
+    if (__builtin_expect(__any(!(sx <= 1.8e19f) || !(sy <= 1.8e19f)), 0)) {     // also true for NaN; wave-uniform
+        lse_refresh(X, scale2, m[0], l[0]);
+        lse_refresh(Y, scale2, m[1], l[1]);
+    } else {
+        l[0] += sx;
+        l[1] += sy;
     }
 }
 
@@ -217,11 +241,13 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                                                  16, 0, 0);
             }
         }
-        if (PASS == 2 && tid < BX)   // negated at store time; rows outside [R0, L) get +inf and contribute nothing
+        // wave 0 = threads 0 .. BX-1, as a scalar test; negated at store time; rows outside [R0, L) get +inf and
+        // contribute nothing
+        if (PASS == 2 && wave == 0)
             stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
     };
     auto store_tile = [&](float* xlb) {
-        if (PASS == 2 && tid < BX) xlb[tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
+        if (PASS == 2 && wave == 0) xlb[tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
@@ -303,8 +329,12 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                 }
                 const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
                 const float* nl = &cur_l[rb * 32 + 4 * half];
-                block_epilogue<PASS, MASK>(Xc, scale2, xb, sA, nl, m[0], l[0], run[0]);
-                block_epilogue<PASS, MASK>(Yc, scale2, xb, sB, nl, m[1], l[1], run[1]);
+                if (PASS == 1) {
+                    lse_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, m, l);
+                } else {
+                    block_epilogue<PASS, MASK>(Xc, scale2, xb, sA, nl, m[0], l[0], run[0]);
+                    block_epilogue<PASS, MASK>(Yc, scale2, xb, sB, nl, m[1], l[1], run[1]);
+                }
             }
         }
         if (it + 1 < n_it) store_tile(nxt_l);
