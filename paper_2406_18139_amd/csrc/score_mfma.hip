@@ -30,32 +30,28 @@ constexpr int XROW = 128;       // LDS row = 256 B, unpadded; the 16-byte chunk 
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// Epilogue of one finished 32x32 block: 16 accumulator entries of this lane = 16 streamed rows
-// against ONE stationary row.
-//   PASS 1: running (max, sum) of 2^(c*s) over the keys of the lane's query row.
-//   PASS 2: running sum of 2^(c*s - lse2_i) over the query rows of the lane's key; nl = -lse2_i of the
-//           16 streamed rows, read from LDS.
-template <int PASS, bool MASK>
-__device__ __forceinline__ void block_epilogue(f32x16 acc, float scale2, int xb, int s, const float* nl,
-                                               float& m, float& l, float& run)
+// Epilogues of the two 32x32 blocks a wave finishes together: the same 32 streamed rows against its two sets of 32
+// stationary rows.  A lane's 16 accumulator entries are 16 streamed rows against ONE stationary row, entry r being
+// streamed row xb + 8*(r/4) + r%4.
+//   PASS 2: running sums of 2^(c*(s - b_i)) over the query rows of the lane's two keys, b_i = lse2_i / c; the
+//           accumulators arrive with -b_i already in them (the MFMA chain starts from it instead of from zero),
+//           so no per-row value has to be held in registers here.
+template <bool MASK>
+__device__ __forceinline__ void colsum_pair_epilogue(const f32x16& X, const f32x16& Y, float scale2, int xb, int sA,
+                                                     int sB, float (&run)[2])
 {
-    if (PASS == 1) {
-        // handled by lse_pair_epilogue, two blocks at a time
-    } else {
-        float sum = 0.f;
+    float sx = 0.f, sy = 0.f;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
-            const float nlv[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float p = __builtin_amdgcn_exp2f(fmaf(acc[4 * g + e], scale2, nlv[e]));
-                if (MASK && (xb + 8 * g + e < s)) p = 0.f;   // query before the key
-                sum += p;
-            }
-        }
-        run += sum;
+    for (int r = 0; r < 16; ++r) {
+        float px = __builtin_amdgcn_exp2f(X[r] * scale2);
+        float py = __builtin_amdgcn_exp2f(Y[r] * scale2);
+        if (MASK && (xb + 8 * (r >> 2) + (r & 3) < sA)) px = 0.f;   // query before the key
+        if (MASK && (xb + 8 * (r >> 2) + (r & 3) < sB)) py = 0.f;
+        sx += px;
+        sy += py;
     }
+    run[0] += sx;
+    run[1] += sy;
 }
 
 // Pass 1, the two finished blocks of a wave (same 32 streamed keys against its two sets of 32 query rows).
@@ -230,13 +226,12 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                 __builtin_amdgcn_global_load_lds(
                     (const __attribute__((address_space(1))) void*)(Xb + (o + (uint32_t)i * 16 * SD * 2)),
                     (__attribute__((address_space(3))) void*)&xsb[(i * 4 + wave) * 4 * XROW], 16, 0, 0);
-        } else {
+        } else {                     // the tensor's last tile: rows past the end re-read the last row
+            const int lane_row = (int)(lane_off >> 8), lane_chunk = (int)(lane_off & 255);   // SD * 2 = 256 bytes per row
 #pragma unroll
             for (int i = 0; i < NLD; ++i) {
-                const int row = (i * 4 + wave) * 4 + ld_sub;                        // row inside the tile
-                const int grow = min(x0 + row, L - 1);
-                const bf16_t* src = X + (size_t)grow * SD + ((ld_pos ^ (row & 7)) * 8);
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                const uint32_t o = (uint32_t)min(x0 + i * 16 + lane_row, L - 1) * (SD * 2) + lane_chunk;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(Xb + o),
                                                  (__attribute__((address_space(3))) void*)&xsb[(i * 4 + wave) * 4 * XROW],
                                                  16, 0, 0);
             }
@@ -247,7 +242,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
     };
     auto store_tile = [&](float* xlb) {
-        if (PASS == 2 && wave == 0) xlb[tid] = -stage_l * lse_scale;   // rows past the end: -inf, they contribute 0
+        if (PASS == 2 && wave == 0) xlb[tid] = -stage_l * lse_scale;   // -lse2_i / c; rows past the end: -inf, they contribute 0
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
@@ -311,29 +306,76 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
         const bool skip = MASK && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
         if (!skip) {
-#pragma unroll 1   // one block of 32 streamed rows at a time keeps the kernel within 168 VGPRs
-            for (int rb = 0; rb < BX / 32; ++rb) {
+            // Two blocks of 32 streamed rows.  The fragments of the second block are fetched into the registers of
+            // the first block's fragments as soon as its MFMAs have been issued, so that the LDS latency passes
+            // under the first block's epilogue; the scheduling barriers keep the compiler from undoing the order
+            // (and from holding more than one block's values at a time: the kernel has to stay within 168 VGPRs).
+            bf16x8 a[8];
+            f32x16 Xc, Yc;
+            // fetch(rb, 0): fragments of dims 0..31 and 64..95 (MFMA steps 0, 1, 4, 5); fetch(rb, 1): the other four
+            auto fetch = [&](int rb, int part) {
                 const bf16_t* ap = &cur[(rb * 32 + n) * XROW];
-                bf16x8 a[8];
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
+                for (int ks = 2 * part; ks < 2 * part + 2; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
                     a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
                     a[ks + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
                 }
-                f32x16 Xc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                f32x16 Yc = Xc;
+            };
+            // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the block's 16 streamed
+            // rows (four 16-byte LDS reads per chain, straight into the accumulator registers) in pass 2
+            auto multiply = [&](int rb, int part) {
+                if (part == 0) {
+                    if (PASS == 1) {
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
+                        for (int r = 0; r < 16; ++r) { Xc[r] = 0.f; Yc[r] = 0.f; }
+                    } else {
+                        const float* nl = &cur_l[rb * 32 + 4 * half];
+#pragma unroll
+                        for (int g = 0; g < 4; ++g) {
+                            const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
+                            Xc[4 * g + 0] = v.x; Xc[4 * g + 1] = v.y; Xc[4 * g + 2] = v.z; Xc[4 * g + 3] = v.w;
+                            Yc[4 * g + 0] = v.x; Yc[4 * g + 1] = v.y; Yc[4 * g + 2] = v.z; Yc[4 * g + 3] = v.w;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int ks = 2 * part; ks < 2 * part + 2; ++ks) {
                     Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
                     Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
+                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks + 4], sf[0][ks + 4], Xc, 0, 0, 0);
+                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks + 4], sf[1][ks + 4], Yc, 0, 0, 0);
                 }
+            };
+            auto epilogue = [&](int rb) {
                 const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
-                const float* nl = &cur_l[rb * 32 + 4 * half];
-                if (PASS == 1) {
-                    lse_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, m, l);
-                } else {
-                    block_epilogue<PASS, MASK>(Xc, scale2, xb, sA, nl, m[0], l[0], run[0]);
-                    block_epilogue<PASS, MASK>(Yc, scale2, xb, sB, nl, m[1], l[1], run[1]);
+                if (PASS == 1) lse_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, m, l);
+                else colsum_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, run);
+            };
+            fetch(0, 0);
+            fetch(0, 1);
+            if (PASS == 1) {
+                multiply(0, 0);
+                multiply(0, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(1, 0);
+                fetch(1, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                epilogue(0);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(1, 0);
+                multiply(1, 1);
+                epilogue(1);
+            } else {
+                // the same schedule as a loop: unrolled, pass 2 does not fit into 168 VGPRs
+#pragma unroll 1
+                for (int rb = 0; rb < BX / 32; ++rb) {
+                    multiply(rb, 0);
+                    multiply(rb, 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (rb == 0) { fetch(1, 0); fetch(1, 1); }
+                    __builtin_amdgcn_sched_barrier(0);
+                    epilogue(rb);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
@@ -497,7 +539,7 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
     hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, group, L, R0, scale2,
-                       C, U2, lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, part_a, part_b, rnorm);
+                       C, U2, lse_in ? lse_in : lse, (lse_in ? lookm::kLog2e : 1.0f) / scale2, part_a, part_b, rnorm);
     mark(LOOKM_K_SCORE_COLSUM);
     hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, kv_heads), dim3(256), 0, st, group, L, R0, C, part_a, part_b,
                        scores);
