@@ -236,13 +236,21 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                                                  16, 0, 0);
             }
         }
-        // wave 0 = threads 0 .. BX-1, as a scalar test; negated at store time; rows outside [R0, L) get +inf and
-        // contribute nothing
-        if (PASS == 2 && wave == 0)
-            stage_l = (x0 + tid < L && x0 + tid >= R0) ? lse_h[x0 + tid] : INFINITY;
+        // Pass 2 also needs lse2 of the tile's rows: wave 0 (threads 0 .. BX-1, a scalar test) loads one value per
+        // lane here, unconditionally (rows outside the tensor read its last row), and store_tile puts it into LDS at
+        // the end of the previous tile.  Nothing may touch the loaded value before that: a use right after the load
+        // would make the wave wait for everything it has just issued, the tile's rows included - hence the empty asm
+        // in store_tile, which keeps the compiler from moving the arithmetic up here.
+        if (PASS == 2 && wave == 0) stage_l = lse_h[min(x0 + tid, L - 1)];
     };
-    auto store_tile = [&](float* xlb) {
-        if (PASS == 2 && wave == 0) xlb[tid] = -stage_l * lse_scale;   // -lse2_i / c; rows past the end: -inf, they contribute 0
+    // x0: first row of the tile that was loaded.  Value stored: -lse2_i / c (the start of the MFMA chains of pass 2);
+    // rows outside [R0, L) get -inf and contribute nothing.
+    auto store_tile = [&](float* xlb, int x0) {
+        if (PASS == 2 && wave == 0) {
+            float v = stage_l;
+            asm volatile("" : "+v"(v));
+            xlb[tid] = (x0 + tid < L && x0 + tid >= R0) ? -v * lse_scale : -INFINITY;
+        }
     };
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
@@ -250,7 +258,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     const int sA = w0 + n, sB = w0 + 32 + n;            // stationary index of this lane for cb = 0, 1
 
     load_tile(x_begin, xs0);
-    store_tile(xl0);
+    store_tile(xl0, x_begin);
     if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0) && h % group == 0) {
         // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
         // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
@@ -291,101 +299,6 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) frag_off[ks] = ((2 * ks + half) ^ (n & 7)) * 8;
 
-    // One tile.  MASK = true evaluates the causal condition per element and is correct for every tile;
-    // MASK = false is the same minus the comparisons, for tiles known to lie entirely inside the causal
-    // region.  Each variant gets a loop of its own below (one code path per loop).
-    auto tile_step = [&](auto mask_tag, auto buf_tag, int it) {
-        constexpr bool MASK = decltype(mask_tag)::value;
-        constexpr int BUF = decltype(buf_tag)::value;
-        bf16_t* cur = BUF ? xs1 : xs0;
-        bf16_t* nxt = BUF ? xs0 : xs1;
-        float* cur_l = BUF ? xl1 : xl0;
-        float* nxt_l = BUF ? xl0 : xl1;
-        const int x0 = x_begin + it * BX;
-        if (it + 1 < n_it) load_tile(x0 + BX, nxt);
-        // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
-        const bool skip = MASK && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
-        if (!skip) {
-            // Two blocks of 32 streamed rows.  The fragments of the second block are fetched into the registers of
-            // the first block's fragments as soon as its MFMAs have been issued, so that the LDS latency passes
-            // under the first block's epilogue; the scheduling barriers keep the compiler from undoing the order
-            // (and from holding more than one block's values at a time: the kernel has to stay within 168 VGPRs).
-            bf16x8 a[8];
-            f32x16 Xc, Yc;
-            // fetch(rb, 0): fragments of dims 0..31 and 64..95 (MFMA steps 0, 1, 4, 5); fetch(rb, 1): the other four
-            auto fetch = [&](int rb, int part) {
-                const bf16_t* ap = &cur[(rb * 32 + n) * XROW];
-#pragma unroll
-                for (int ks = 2 * part; ks < 2 * part + 2; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
-                    a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
-                    a[ks + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
-                }
-            };
-            // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the block's 16 streamed
-            // rows (four 16-byte LDS reads per chain, straight into the accumulator registers) in pass 2
-            auto multiply = [&](int rb, int part) {
-                if (part == 0) {
-                    if (PASS == 1) {
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) { Xc[r] = 0.f; Yc[r] = 0.f; }
-                    } else {
-                        const float* nl = &cur_l[rb * 32 + 4 * half];
-#pragma unroll
-                        for (int g = 0; g < 4; ++g) {
-                            const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
-                            Xc[4 * g + 0] = v.x; Xc[4 * g + 1] = v.y; Xc[4 * g + 2] = v.z; Xc[4 * g + 3] = v.w;
-                            Yc[4 * g + 0] = v.x; Yc[4 * g + 1] = v.y; Yc[4 * g + 2] = v.z; Yc[4 * g + 3] = v.w;
-                        }
-                    }
-                }
-#pragma unroll
-                for (int ks = 2 * part; ks < 2 * part + 2; ++ks) {
-                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
-                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
-                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks + 4], sf[0][ks + 4], Xc, 0, 0, 0);
-                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks + 4], sf[1][ks + 4], Yc, 0, 0, 0);
-                }
-            };
-            auto epilogue = [&](int rb) {
-                const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
-                if (PASS == 1) lse_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, m, l);
-                else colsum_pair_epilogue<MASK>(Xc, Yc, scale2, xb, sA, sB, run);
-            };
-            fetch(0, 0);
-            fetch(0, 1);
-            if (PASS == 1) {
-                multiply(0, 0);
-                multiply(0, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                fetch(1, 0);
-                fetch(1, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                epilogue(0);
-                __builtin_amdgcn_sched_barrier(0);
-                multiply(1, 0);
-                multiply(1, 1);
-                epilogue(1);
-            } else {
-                // the same schedule as a loop: unrolled, pass 2 does not fit into 168 VGPRs
-#pragma unroll 1
-                for (int rb = 0; rb < BX / 32; ++rb) {
-                    multiply(rb, 0);
-                    multiply(rb, 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (rb == 0) { fetch(1, 0); fetch(1, 1); }
-                    __builtin_amdgcn_sched_barrier(0);
-                    epilogue(rb);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-        }
-        if (it + 1 < n_it) store_tile(nxt_l);
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the next tile's direct-to-LDS loads have landed
-        __syncthreads();
-    };
-    using masked = std::integral_constant<bool, true>;
-    using plain = std::integral_constant<bool, false>;
-
     // Which tiles need the mask (wave-uniform, so the choice is a scalar branch):
     //   pass 1, keys stream upwards: tiles with x0 + BX - 1 <= w0 hold only keys at or before every query row of
     //   this wave, the tiles after them touch the diagonal;
@@ -400,13 +313,113 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         plain_from = max(0, min(n_masked, n_it));
         plain_to = n_it;
     }
-    auto one_tile = [&](auto buf_tag, int it) {
-        if (it >= plain_from && it < plain_to) tile_step(plain{}, buf_tag, it);
-        else tile_step(masked{}, buf_tag, it);
+    // fragments of one block of 32 streamed rows (the A operands of its 16 MFMAs), fetched one block ahead
+    bf16x8 a[8];
+    auto fetch = [&](const bf16_t* tile_rows, int rb) {
+        const bf16_t* ap = &tile_rows[(rb * 32 + n) * XROW];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
+            a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
+            a[ks + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
+        }
+    };
+    if (n_it > 0) fetch(xs0, 0);
+
+    // One tile, with its LDS buffer known at compile time.  Tiles that touch the diagonal evaluate the causal
+    // condition per element in their epilogues; tiles known to lie entirely inside the causal region run the same
+    // epilogue minus the comparisons.  The choice is wave-uniform and made by a scalar branch around the epilogue
+    // only, so that there is one tile body per buffer (with a body per mask variant the fragments carried from one
+    // tile to the next would have to meet in the same registers on four paths, and the kernel no longer fits).
+    auto tile_step = [&](auto buf_tag, int it) {
+        constexpr int BUF = decltype(buf_tag)::value;
+        bf16_t* cur = BUF ? xs1 : xs0;
+        bf16_t* nxt = BUF ? xs0 : xs1;
+        float* cur_l = BUF ? xl1 : xl0;
+        float* nxt_l = BUF ? xl0 : xl1;
+        const int x0 = x_begin + it * BX;
+        if (it + 1 < n_it) load_tile(x0 + BX, nxt);
+        // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
+        const bool mask = !(it >= plain_from && it < plain_to);
+        const bool skip = mask && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
+
+        // End of the tile's LDS reads: wait for the next tile's loads, meet the other waves, and fetch the next
+        // tile's first fragments - before the epilogue of this tile's second block, which hides their latency.
+        auto finish_tile = [&]() {
+            if (it + 1 < n_it) store_tile(nxt_l, x0 + BX);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the next tile's direct-to-LDS loads have landed
+            __syncthreads();
+            fetch(nxt, 0);   // unconditional: after the last tile this reads an old tile and the values are never used
+        };
+        if (!skip) {
+            // Two blocks of 32 streamed rows; the fragments of block 0 are in `a` already (fetched by the previous
+            // tile, or before the loop).  A block's fragments are dead once its MFMAs have been issued, so the next
+            // block's are fetched into the same registers right away and their LDS latency passes under the
+            // epilogue.  The scheduling barriers keep the compiler from undoing the order, and from holding more
+            // than one block's values at a time: the kernel has to stay within 168 VGPRs.
+            f32x16 Xc, Yc;
+            // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the block's 16 streamed
+            // rows (four 16-byte LDS reads per chain, straight into the accumulator registers) in pass 2
+            auto multiply = [&](int rb) {
+                if (PASS == 1) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) { Xc[r] = 0.f; Yc[r] = 0.f; }
+                } else {
+                    const float* nl = &cur_l[rb * 32 + 4 * half];
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
+                        Xc[4 * g + 0] = v.x; Xc[4 * g + 1] = v.y; Xc[4 * g + 2] = v.z; Xc[4 * g + 3] = v.w;
+                        Yc[4 * g + 0] = v.x; Yc[4 * g + 1] = v.y; Yc[4 * g + 2] = v.z; Yc[4 * g + 3] = v.w;
+                    }
+                }
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
+                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
+                }
+            };
+            auto epilogue = [&](int rb) {
+                const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
+                if (mask) {      // a scalar branch; both sides leave the prefetched fragments alone
+                    if (PASS == 1) lse_pair_epilogue<true>(Xc, Yc, scale2, xb, sA, sB, m, l);
+                    else colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, sA, sB, run);
+                } else {
+                    if (PASS == 1) lse_pair_epilogue<false>(Xc, Yc, scale2, xb, sA, sB, m, l);
+                    else colsum_pair_epilogue<false>(Xc, Yc, scale2, xb, sA, sB, run);
+                }
+            };
+            if (PASS == 1) {
+                multiply(0);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(cur, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                epilogue(0);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply(1);
+                __builtin_amdgcn_sched_barrier(0);
+                finish_tile();
+                __builtin_amdgcn_sched_barrier(0);
+                epilogue(1);
+            } else {
+                // the same schedule as a loop: unrolled, pass 2 does not fit into 168 VGPRs
+#pragma unroll 1
+                for (int rb = 0; rb < BX / 32; ++rb) {
+                    multiply(rb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (rb == 0) fetch(cur, 1);
+                    else finish_tile();
+                    __builtin_amdgcn_sched_barrier(0);
+                    epilogue(rb);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        } else {
+            finish_tile();
+        }
     };
     for (int it = 0; it < n_it; it += 2) {
-        one_tile(std::integral_constant<int, 0>{}, it);
-        if (it + 1 < n_it) one_tile(std::integral_constant<int, 1>{}, it + 1);
+        tile_step(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < n_it) tile_step(std::integral_constant<int, 1>{}, it + 1);
     }
 
     // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
