@@ -125,9 +125,10 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT, int 
     return (L + CT - 1) / CT - max(t * BS, R0) / CT;
 }
 
-// The matrix pipe and the vector ALU of a SIMD overlap ACROSS waves, not within one (measured: an MFMA
-// followed by independent VALU work in the same wave runs back to back), so the kernel keeps each
-// wave's code simple - MFMA chains, then the epilogue - and is sized for three resident waves per SIMD.
+// The matrix pipe and the vector ALU of a SIMD overlap ACROSS waves far better than within one (measured), so a
+// wave's arithmetic stays in two phases - MFMA chains, then the epilogue - and the kernel is sized for three
+// resident waves per SIMD; what a wave does overlap with its own arithmetic is memory latency (LDS fragment
+// fetches one block ahead, tile loads one tile ahead).
 //   PASS 1 writes part_a = running max, part_b = running sum (base-2 domain) per (chunk, stationary row).
 //   PASS 2 writes part_a = partial column sum per (chunk, stationary row).  Its stationary rows are keys: when
 //   `rnorm` is given, the workgroup of a strip's first chunk also writes rnorm[h, j] = 1 / ||k_j|| (0 for a
