@@ -57,14 +57,16 @@ def stack(args) -> int:
     dev = torch.device("cuda:0")
     prompts = W.stack_prompts()
     layers = W.STACK_LAYERS
-    jobs = []
+    per_prompt = []
     for w in prompts:
         B = w.budget()
         out = lookm.alloc_outputs(w.H, w.L, w.d, B, w.torch_dtype(), dev)
         ws = lookm.alloc_workspace(w.H, w.L, w.d, B, lookm.BF16, dev)
-        for layer in range(layers):
-            q, k, v, mask = W.generate_on_device(w, layer, dev)
-            jobs.append((w, B, q, k, v, mask, out, ws))
+        per_prompt.append([(w, B, *W.generate_on_device(w, layer, dev), out, ws) for layer in range(layers)])
+    # Layer-major order, as a prefill produces the caches: layer 0 of every prompt, then layer 1, ...  The layers of a
+    # prompt share its workspace and outputs and therefore run in order; different prompts are independent, and the
+    # library runs them on two lanes (see lookm_compress_batch).
+    jobs = [per_prompt[p][layer] for layer in range(layers) for p in range(len(prompts))]
     torch.cuda.synchronize()
     batch = [lookm.make_job(q, k, v, mask, B, w.M, "weighted", out, ws) for w, B, q, k, v, mask, out, ws in jobs]
 
@@ -79,7 +81,7 @@ def stack(args) -> int:
         step()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) / args.steps * 1e3
-    bad = [int(j[6].status.item()) for j in jobs[::layers]]
+    bad = [int(pp[0][6].status.item()) for pp in per_prompt]
     if any(bad):
         print(f"bench.py: device status {bad}", file=sys.stderr)
         return 1

@@ -244,15 +244,25 @@ typedef struct lookm_job {
     int32_t* kept_idx;
     float* scores_out;               /* or NULL */
     int32_t* status_out;             /* one word per job (jobs may not share it) */
-    void* workspace;                 /* jobs of one call run one after the other on the stream and may share it */
+    void* workspace;                 /* jobs may share it: jobs whose memory overlaps run in the order given */
     size_t workspace_bytes;
 } lookm_job;
 
 /*
  * The whole path for n_jobs (prompt, layer) pairs - e.g. the 32 layers of each prompt of a batch, of
- * different lengths - enqueued in order on one stream.  EVERY job is validated before the first launch:
- * on an invalid job nothing is enqueued, the return value is that job's error and *bad_job (if not NULL)
- * its index.  n_jobs = 0 is a no-op.
+ * different lengths.  EVERY job is validated before the first launch: on an invalid job nothing is enqueued,
+ * the return value is that job's error and *bad_job (if not NULL) its index.  n_jobs = 0 is a no-op.
+ *
+ * Order and streams.  The result is what running the jobs one after the other in the order given would give.  Jobs
+ * that touch disjoint memory need not wait for each other, though: the library alternates such jobs between
+ * hip_stream and ONE stream of its own (default priority, created on first use, one per device, kept until the
+ * process ends), so that the short latency-bound kernels of one job run under the long kernels of another.  Two jobs
+ * are kept in order whenever one writes (workspace, k_out, v_out, kept_idx, scores_out, status_out) what the other
+ * reads or writes; give independent prompts their own workspace and outputs to let them overlap, and pass the jobs in
+ * the order a prefill produces them (layer 0 of every prompt, then layer 1, ...).  All work of the call starts after
+ * the work already enqueued on hip_stream and is complete before anything enqueued on hip_stream afterwards (event
+ * fork / join; no host synchronisation).  When hip_stream is being captured into a graph the jobs are simply
+ * enqueued in order on hip_stream.  Calls from several host threads are serialised by a lock.
  */
 int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream);
 

@@ -4,6 +4,8 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
+#include <vector>
 
 namespace {
 
@@ -65,6 +67,168 @@ int check_workspace(const void* ws, size_t bytes, int Hq, int H, int L, int d, i
 }
 
 template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*>(static_cast<char*>(base) + off); }
+
+// ---- two lanes for independent jobs of a batch -----------------------------------------------------------
+// Jobs that touch disjoint memory do not have to wait for each other: alternating them between the caller's
+// stream and one stream of the library lets the short, latency-bound kernels of one job (selection, set sort,
+// folds) and the tail of its long kernels run under the long kernels of the next.  Everything stays ordered
+// after the work already on the caller's stream and before the work the caller enqueues next (fork / join with
+// events); jobs that share a workspace or an output keep their order.
+
+struct ByteRange {
+    uintptr_t lo, hi;   // [lo, hi)
+};
+struct JobFootprint {
+    ByteRange w[6], r[5];   // what the job writes / only reads
+    int nw, nr;
+};
+
+inline void add_range(ByteRange* list, int& n, const void* p, size_t bytes)
+{
+    if (p == nullptr || bytes == 0) return;
+    list[n].lo = reinterpret_cast<uintptr_t>(p);
+    list[n].hi = list[n].lo + bytes;
+    ++n;
+}
+
+JobFootprint footprint(const lookm_job& j)
+{
+    const size_t Hq = (size_t)j.H, H = (size_t)(j.kv_heads ? j.kv_heads : j.H), L = (size_t)j.L, d = (size_t)j.d,
+                 B = (size_t)j.budget, es = (j.dt == LOOKM_BF16) ? 2 : 4;
+    JobFootprint f;
+    f.nw = f.nr = 0;
+    add_range(f.w, f.nw, j.workspace, j.workspace_bytes);
+    add_range(f.w, f.nw, j.k_out, H * B * d * es);
+    add_range(f.w, f.nw, j.v_out, H * B * d * es);
+    add_range(f.w, f.nw, j.kept_idx, H * B * sizeof(int32_t));
+    add_range(f.w, f.nw, j.scores_out, H * L * sizeof(float));
+    add_range(f.w, f.nw, j.status_out, sizeof(int32_t));
+    add_range(f.r, f.nr, j.q, Hq * L * d * es);
+    add_range(f.r, f.nr, j.k, H * L * d * es);
+    add_range(f.r, f.nr, j.v, H * L * d * es);
+    add_range(f.r, f.nr, j.modality_mask, L);
+    add_range(f.r, f.nr, j.row_lse, Hq * L * sizeof(float));
+    return f;
+}
+
+inline bool overlap(const ByteRange& a, const ByteRange& b) { return a.lo < b.hi && b.lo < a.hi; }
+
+// true if the two jobs may not run at the same time: one writes what the other reads or writes
+bool conflict(const JobFootprint& a, const JobFootprint& b)
+{
+    for (int i = 0; i < a.nw; ++i) {
+        for (int k = 0; k < b.nw; ++k) if (overlap(a.w[i], b.w[k])) return true;
+        for (int k = 0; k < b.nr; ++k) if (overlap(a.w[i], b.r[k])) return true;
+    }
+    for (int i = 0; i < a.nr; ++i)
+        for (int k = 0; k < b.nw; ++k) if (overlap(a.r[i], b.w[k])) return true;
+    return false;
+}
+
+// the library's second stream and its events, one set per device, created on first use and kept until the process
+// ends (default priority, like every stream here)
+struct SideLane {
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> events;
+    size_t used = 0;
+    bool failed = false;
+};
+constexpr int kMaxDevices = 64;
+SideLane g_side[kMaxDevices];
+std::mutex g_side_mutex;
+
+hipEvent_t next_event(SideLane& s)
+{
+    if (s.used == s.events.size()) {
+        hipEvent_t e = nullptr;
+        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        s.events.push_back(e);
+    }
+    return s.events[s.used++];
+}
+
+// `later` waits for everything enqueued on `earlier` so far
+bool order_after(SideLane& s, hipStream_t earlier, hipStream_t later)
+{
+    hipEvent_t e = next_event(s);
+    return e != nullptr && hipEventRecord(e, earlier) == hipSuccess && hipStreamWaitEvent(later, e, 0) == hipSuccess;
+}
+
+int enqueue_job(const lookm_job& j, hipStream_t st);
+
+int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t main)
+{
+    auto serial = [&](int from) {
+        for (int i = from; i < n_jobs; ++i) {
+            const int rc = enqueue_job(jobs[i], main);
+            if (rc != LOOKM_OK) {                 // only a failing HIP runtime call can end up here
+                if (bad_job) *bad_job = i;
+                return rc;
+            }
+        }
+        return (int)LOOKM_OK;
+    };
+    int dev = 0;
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    // one job, a stream under graph capture (no stream or event is created while a capture is open), or an unknown
+    // device: the plain loop
+    if (n_jobs < 2 || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices ||
+        hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone)
+        return serial(0);
+
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideLane& side = g_side[dev];
+    if (side.stream == nullptr && !side.failed &&
+        hipStreamCreateWithFlags(&side.stream, hipStreamNonBlocking) != hipSuccess) {
+        side.stream = nullptr;
+        side.failed = true;
+        (void)hipGetLastError();
+    }
+    if (side.stream == nullptr) return serial(0);
+    side.used = 0;
+
+    hipStream_t lane[2] = {main, side.stream};
+    // jobs of a lane that the other lane has not been ordered after yet; before the fork only the caller's lane
+    // exists, and the fork itself orders the side lane after all of it
+    std::vector<JobFootprint> open[2];
+    bool forked = false;
+    int rc = LOOKM_OK, bad = 0;
+    for (int i = 0; i < n_jobs && rc == LOOKM_OK; ++i) {
+        bad = i;
+        const JobFootprint f = footprint(jobs[i]);
+        bool hit[2] = {false, false};
+        for (int l = 0; l < 2; ++l)
+            for (const JobFootprint& o : open[l])
+                if (conflict(f, o)) { hit[l] = true; break; }
+        // alternate; a job that depends on one lane only follows it there (stream order, no event needed)
+        int want = i & 1;
+        if (hit[0] != hit[1]) want = hit[0] ? 0 : 1;
+        const int other = 1 - want;
+        if (want == 1 && !forked) {           // the side lane starts after the work already on the caller's stream
+            if (!order_after(side, main, side.stream)) { rc = LOOKM_ERR_DEVICE; break; }
+            forked = true;
+            open[0].clear();
+        }
+        if (hit[other]) {                     // depends on both lanes: wait for the other one here
+            if (!order_after(side, lane[other], lane[want])) { rc = LOOKM_ERR_DEVICE; break; }
+            open[other].clear();
+        }
+        rc = enqueue_job(jobs[i], lane[want]);
+        open[want].push_back(f);
+        if (open[want].size() >= 64) {        // keep the lists short: let the other lane catch up with this one
+            if (forked) {
+                if (!order_after(side, lane[want], lane[other])) { rc = LOOKM_ERR_DEVICE; break; }
+                open[want].clear();
+            } else {
+                open[want].erase(open[want].begin());
+            }
+        }
+    }
+    // join: whatever the caller enqueues next comes after both lanes
+    if (forked && !order_after(side, side.stream, main) && rc == LOOKM_OK) rc = LOOKM_ERR_DEVICE;
+    if (rc != LOOKM_OK && bad_job) *bad_job = bad;
+    return rc;
+}
 
 }  // namespace
 
@@ -239,7 +403,10 @@ static int validate_job(const lookm_job& j)
 }
 
 // the launch sequence of one validated job
-static int enqueue_job(const lookm_job& j, hipStream_t st)
+}  // extern "C"
+
+namespace {
+int enqueue_job(const lookm_job& j, hipStream_t st)
 {
     // Hq query heads; everything after the scores runs per key / value head
     const int Hq = j.H, H = j.kv_heads ? j.kv_heads : j.H, L = j.L, d = j.d, budget = j.budget;
@@ -272,6 +439,9 @@ static int enqueue_job(const lookm_job& j, hipStream_t st)
                                     at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), j.k_out, j.v_out, st);
 }
+}  // namespace
+
+extern "C" {
 
 static int compress_impl(const void* q, const void* k, const void* v, const uint8_t* modality_mask,
                          const float* row_lse, int H, int L, int d, lookm_dtype dt, int budget, int recent_window,
@@ -319,14 +489,8 @@ int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* 
             return rc;
         }
     }
-    for (int i = 0; i < n_jobs; ++i) {
-        const int rc = enqueue_job(jobs[i], (hipStream_t)hip_stream);
-        if (rc != LOOKM_OK) {                 // only a failing HIP runtime call can end up here
-            if (bad_job) *bad_job = i;
-            return rc;
-        }
-    }
-    return LOOKM_OK;
+    const int rc = enqueue_batch(jobs, n_jobs, bad_job, (hipStream_t)hip_stream);
+    return rc;
 }
 
 size_t lookm_decode_workspace_bytes(int H, int d)

@@ -204,6 +204,68 @@ def test_batch_call_equals_single_calls():
     assert e.value.code == lookm.ERR_BUDGET_RANGE and "job 1" in str(e.value)
 
 
+def test_batch_runs_independent_jobs_on_two_lanes_and_keeps_dependent_ones_in_order():
+    """Jobs with disjoint memory may run at the same time (the library alternates them between the caller's stream
+    and one of its own); jobs that share a workspace, or read what an earlier job writes, keep their order.  Either
+    way every job must give exactly what it gives alone."""
+    w = W.LLAVA7B
+    dev = torch.device("cuda:0")
+    B, M = w.budget(), w.M
+    layers = []
+    for i in range(6):
+        q, k, v, mask = W.generate(w, heads=[i, i + 8, i + 16])
+        layers.append(tuple(t.to(dev) for t in (q, k, v, mask)))
+    single = [lookm.lookm_compress(*t, B, M, "weighted") for t in layers]
+    H, L, d = layers[0][0].shape
+    dt = lookm._dt(layers[0][0])
+
+    def check(outs):
+        torch.cuda.synchronize()
+        for a, b in zip(single, outs):
+            assert int(b.status.item()) == 0
+            assert torch.equal(a.kept_idx, b.kept_idx)
+            assert torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out)
+
+    # (1) a workspace per job: all six independent
+    outs = [lookm.alloc_outputs(H, L, d, B, layers[0][0].dtype, dev) for _ in layers]
+    wss = [lookm.alloc_workspace(H, L, d, B, dt, dev) for _ in layers]
+    for rep in range(3):
+        for o in outs:
+            o.k_out.zero_(); o.kept_idx.zero_(); o.status.fill_(-99)
+        lookm.lookm_compress_batch([lookm.make_job(*t, B, M, "weighted", o, x) for t, o, x in zip(layers, outs, wss)])
+        check(outs)
+    # (2) two workspaces taken in turn (prompt-interleaved order): jobs 0, 2, 4 and 1, 3, 5 are chains
+    outs = [lookm.alloc_outputs(H, L, d, B, layers[0][0].dtype, dev) for _ in layers]
+    lookm.lookm_compress_batch([lookm.make_job(*t, B, M, "weighted", o, wss[i % 2])
+                                for i, (t, o) in enumerate(zip(layers, outs))])
+    check(outs)
+    # (3) chains in blocks (prompt-major order): jobs 0, 1, 2 share a workspace, jobs 3, 4, 5 the other
+    outs = [lookm.alloc_outputs(H, L, d, B, layers[0][0].dtype, dev) for _ in layers]
+    lookm.lookm_compress_batch([lookm.make_job(*t, B, M, "weighted", o, wss[i // 3])
+                                for i, (t, o) in enumerate(zip(layers, outs))])
+    check(outs)
+    # (4) a job that reads what the job before it writes: the compact cache of job 0, compressed again
+    q2 = layers[1][0][:, :B].contiguous()
+    mask2 = torch.ones(B, dtype=torch.uint8, device=dev)
+    B2 = B // 2
+    first = lookm.alloc_outputs(H, L, d, B, q2.dtype, dev)
+    second = lookm.alloc_outputs(H, B, d, B2, q2.dtype, dev)
+    ref_second = lookm.lookm_compress(q2, single[0].k_out, single[0].v_out, mask2, B2, M, "averaged")
+    lookm.lookm_compress_batch([lookm.make_job(*layers[0], B, M, "weighted", first, wss[0]),
+                                lookm.make_job(q2, first.k_out, first.v_out, mask2, B2, M, "averaged", second, wss[1])])
+    torch.cuda.synchronize()
+    assert int(second.status.item()) == 0
+    assert torch.equal(second.kept_idx, ref_second.kept_idx) and torch.equal(second.k_out, ref_second.k_out)
+    assert torch.equal(second.v_out, ref_second.v_out)
+    # work enqueued after the call sees the results of both lanes without a host synchronisation
+    outs = [lookm.alloc_outputs(H, L, d, B, layers[0][0].dtype, dev) for _ in layers]
+    lookm.lookm_compress_batch([lookm.make_job(*t, B, M, "weighted", o, x) for t, o, x in zip(layers, outs, wss)])
+    copies = [o.k_out.clone() for o in outs]          # on the caller's stream, right behind the batch
+    torch.cuda.synchronize()
+    for a, c in zip(single, copies):
+        assert torch.equal(a.k_out, c)
+
+
 def test_compress_with_an_observation_window():
     # scores from the last 64 query rows only; everything downstream unchanged
     w = W.LLAVA7B
