@@ -172,9 +172,12 @@ int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t m
     hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
     // one job, a stream under graph capture (no stream or event is created while a capture is open), or an unknown
     // device: the plain loop
-    if (n_jobs < 2 || hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices ||
-        hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone)
+    if (n_jobs < 2) return serial(0);
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices ||
+        hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();   // a failed query must not be taken for a failed launch later
         return serial(0);
+    }
 
     std::lock_guard<std::mutex> lock(g_side_mutex);
     SideLane& side = g_side[dev];

@@ -77,3 +77,37 @@ def test_decode_replays_in_a_hip_graph():
     graph.replay()
     torch.cuda.synchronize()
     assert torch.equal(out, ref2)
+
+
+def test_batch_replays_in_a_hip_graph():
+    """Under capture the batch call creates no stream or event: its jobs go onto the captured stream in order."""
+    w = W.LLAVA7B
+    dev = torch.device("cuda:0")
+    B, M = w.budget(), w.M
+    layers = []
+    for i in range(3):
+        q, k, v, mask = W.generate(w, heads=[i, i + 5])
+        layers.append(tuple(t.to(dev) for t in (q, k, v, mask)))
+    H, L, d = layers[0][0].shape
+    ref = [lookm.lookm_compress(*t, B, M, "pivotal") for t in layers]
+    outs = [lookm.alloc_outputs(H, L, d, B, layers[0][0].dtype, dev) for _ in layers]
+    wss = [lookm.alloc_workspace(H, L, d, B, lookm._dt(layers[0][0]), dev) for _ in layers]
+    jobs = [lookm.make_job(*t, B, M, "pivotal", o, x) for t, o, x in zip(layers, outs, wss)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        lookm.lookm_compress_batch(jobs)            # warm-up on a side stream (two lanes here)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lookm.lookm_compress_batch(jobs)
+    for rep in range(3):
+        for o in outs:
+            o.k_out.zero_(); o.v_out.zero_(); o.kept_idx.zero_(); o.status.fill_(-99)
+        _eager_noise(dev)
+        graph.replay()
+        torch.cuda.synchronize()
+        for a, b in zip(ref, outs):
+            assert int(b.status.item()) == 0, rep
+            assert torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out), rep
