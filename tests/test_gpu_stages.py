@@ -38,6 +38,18 @@ def test_scores_match_oracle(H, L, d, dtype):
     np.testing.assert_allclose(s.sum(1), L, rtol=1e-5)
 
 
+@pytest.mark.parametrize("L", [2, 31, 63, 64, 127, 128, 129, 191, 255, 257, 320, 511, 513, 767, 1023, 1025, 1300])
+def test_scores_around_tile_and_strip_boundaries(L):
+    """Lengths on both sides of the 32-row block, 64-row tile and 256-row strip boundaries of the matrix-core
+    kernels: ragged last tiles, waves with nothing to do, tiles skipped above the diagonal."""
+    q, k = rand_qk(2, L, 128, torch.bfloat16, seed=1000 + L)
+    s = lookm.lookm_scores(q.cuda(), k.cuda()).cpu().numpy().astype(np.float64)
+    ref = oracle.scores(q, k)
+    assert np.all(np.isfinite(s))
+    assert (np.abs(s - ref) / ref).max() < 2e-5
+    np.testing.assert_allclose(s.sum(1), L, rtol=1e-5)
+
+
 def test_scores_large_logits_and_determinism():
     q, k = rand_qk(2, 600, 128, torch.bfloat16, seed=5, scale=4.0)   # logits up to ~ +-60
     a = lookm.lookm_scores(q.cuda(), k.cuda())
