@@ -266,6 +266,31 @@ def test_batch_runs_independent_jobs_on_two_lanes_and_keeps_dependent_ones_in_or
         assert torch.equal(a.k_out, c)
 
 
+def test_batch_of_many_small_jobs():
+    """150 jobs over three workspaces taken in turn: three chains, more jobs than the library keeps footprints for
+    before it lets one lane catch up with the other."""
+    w = W.TINY
+    dev = torch.device("cuda:0")
+    B, M = w.budget(), w.M
+    q, k, v, mask = W.generate(w)
+    H, L, d = q.shape
+    mg = mask.to(dev)
+    g = torch.Generator().manual_seed(77)
+    inputs = []
+    for i in range(150):
+        qq = (q + 0.05 * torch.randn(q.shape, generator=g)).to(dev)
+        inputs.append((qq, k.to(dev), v.to(dev), mg))
+    single = [lookm.lookm_compress(*t, B, M, "pivotal") for t in inputs]
+    outs = [lookm.alloc_outputs(H, L, d, B, q.dtype, dev) for _ in inputs]
+    wss = [lookm.alloc_workspace(H, L, d, B, lookm.F32, dev) for _ in range(3)]
+    lookm.lookm_compress_batch([lookm.make_job(*t, B, M, "pivotal", o, wss[i % 3])
+                                for i, (t, o) in enumerate(zip(inputs, outs))])
+    torch.cuda.synchronize()
+    for a, b in zip(single, outs):
+        assert int(b.status.item()) == 0
+        assert torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out)
+
+
 def test_compress_with_an_observation_window():
     # scores from the last 64 query rows only; everything downstream unchanged
     w = W.LLAVA7B
