@@ -20,9 +20,11 @@
  *     ordinary host memory.  Nothing here takes or returns framework types.
  *   - Tensors are dense, row-major, innermost stride 1: q, k, v are [H, L, d] (row stride d,
  *     head stride L*d).  Device tensor pointers must be 16-byte aligned.
- *   - The library allocates and frees nothing: inputs, outputs and the scratch `workspace` are
+ *   - The library allocates and frees no memory: inputs, outputs and the scratch `workspace` are
  *     owned by the caller; inputs are never written.  All work is enqueued on `hip_stream`
- *     (a hipStream_t passed as void*, NULL = the default stream); calls do not synchronise.
+ *     (a hipStream_t passed as void*, NULL = the default stream) - lookm_compress_batch may also use
+ *     one stream of the library, ordered against hip_stream by events - and calls do not synchronise
+ *     (the measurement aids at the end of this header do, and say so).
  *   - The return value reports everything the host can check (negative lookm_status); those checks
  *     run before any kernel is launched and need no GPU.  The one check that needs device data
  *     (budget smaller than the number of protected positions) is reported through `status_out`.
