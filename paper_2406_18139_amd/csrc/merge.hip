@@ -243,25 +243,35 @@ k_merge(const T* __restrict__ k, const T* __restrict__ v, const int32_t* __restr
             for (int i = 0; i < 8; ++i) acc[s][i] = 0.f;
         const bool weighted = (mode == LOOKM_MERGE_WEIGHTED);
         const int o1 = o0 + n;
-        for (int t = o0; t < o1; t += NB) {          // ascending position
-            int p[NB];
-            float w[NB], xe[NT][NB][8];
+        // positions and weights of a batch are fetched one batch ahead, so that a long set costs one memory round
+        // trip per batch (the rows) instead of two dependent ones (positions, then rows)
+        int p[NB];
+        float w[NB];
+        auto fetch_members = [&](int t) {
 #pragma unroll
             for (int j = 0; j < NB; ++j) {
                 const int tt = min(t + j, o1 - 1);
                 p[j] = member_pos[tt];
                 w[j] = (t + j < o1) ? (weighted ? member_w[tt] : 1.0f) : 0.0f;
             }
+        };
+        fetch_members(o0);
+        for (int t = o0; t < o1; t += NB) {          // ascending position
+            float xe[NT][NB][8];
 #pragma unroll
             for (int j = 0; j < NB; ++j)
 #pragma unroll
                 for (int s = 0; s < NT; ++s) load8(x[s] + (size_t)p[j] * d, xe[s][j]);
+            float wc[NB];
+#pragma unroll
+            for (int j = 0; j < NB; ++j) wc[j] = w[j];
+            if (t + NB < o1) fetch_members(t + NB);  // in flight together with this batch's rows
 #pragma unroll
             for (int j = 0; j < NB; ++j)
 #pragma unroll
                 for (int s = 0; s < NT; ++s)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[s][i] = fmaf(xe[s][j][i], w[j], acc[s][i]);
+                    for (int i = 0; i < 8; ++i) acc[s][i] = fmaf(xe[s][j][i], wc[j], acc[s][i]);
         }
         const float inv = 1.0f / (float)(n + 1);
 #pragma unroll
