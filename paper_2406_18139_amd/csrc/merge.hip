@@ -180,10 +180,25 @@ k_bucket(const int32_t* __restrict__ assign, const int32_t* __restrict__ evicted
     };
     if (n_own > 0) place(lane < n_own, pre_key[0], pre_pos[0], pre_w[0]);
     if (n_own > 64) place(64 + lane < n_own, pre_key[1], pre_pos[1], pre_w[1]);
-    for (int c0 = 128; c0 < n_own; c0 += 64) {
-        const bool valid = c0 + lane < n_own;
-        const int e = min(seg + (valid ? (int)own[c0 + lane] : 0), Le - 1);
-        place(valid, assign[e], evicted[e], sim[e]);
+    // further rows (a segment that most of the wave's entries belong to - few slots hold most members): each row's
+    // slot, position and cosine are fetched while the row before it is being placed
+    if (n_own > 128) {
+        auto fetch_row = [&](int c0, int& key, int& pos, float& sw) {
+            const bool valid = c0 + lane < n_own;
+            const int e = min(seg + (valid ? (int)own[c0 + lane] : 0), Le - 1);
+            key = assign[e];
+            pos = evicted[e];
+            sw = sim[e];
+        };
+        int key, pos;
+        float sw;
+        fetch_row(128, key, pos, sw);
+        for (int c0 = 128; c0 < n_own; c0 += 64) {
+            const int ck = key, cp = pos;
+            const float cw = sw;
+            if (c0 + 64 < n_own) fetch_row(c0 + 64, key, pos, sw);
+            place(c0 + lane < n_own, ck, cp, cw);
+        }
     }
 }
 
