@@ -359,22 +359,25 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             // than one block's values at a time: the kernel has to stay within 168 VGPRs.
             f32x16 Xc, Yc;
             // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the block's 16 streamed
-            // rows (four 16-byte LDS reads per chain, straight into the accumulator registers) in pass 2
+            // rows (four 16-byte LDS reads, straight into the first chain's accumulator registers) in pass 2
             auto multiply = [&](int rb) {
                 if (PASS == 1) {
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) { Xc[r] = 0.f; Yc[r] = 0.f; }
+                    for (int r = 0; r < 16; ++r) Xc[r] = 0.f;
                 } else {
                     const float* nl = &cur_l[rb * 32 + 4 * half];
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
                         const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
                         Xc[4 * g + 0] = v.x; Xc[4 * g + 1] = v.y; Xc[4 * g + 2] = v.z; Xc[4 * g + 3] = v.w;
-                        Yc[4 * g + 0] = v.x; Yc[4 * g + 1] = v.y; Yc[4 * g + 2] = v.z; Yc[4 * g + 3] = v.w;
                     }
                 }
+                // both chains start from the same values: the second chain's first MFMA takes them from the first
+                // chain's registers (as its C operand) before the first chain overwrites them
+                Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], sf[1][0], Xc, 0, 0, 0);
+                Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], sf[0][0], Xc, 0, 0, 0);
 #pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
+                for (int ks = 1; ks < 8; ++ks) {
                     Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
                     Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
                 }
