@@ -22,9 +22,10 @@
  *     head stride L*d).  Device tensor pointers must be 16-byte aligned.
  *   - The library allocates and frees no memory: inputs, outputs and the scratch `workspace` are
  *     owned by the caller; inputs are never written.  All work is enqueued on `hip_stream`
- *     (a hipStream_t passed as void*, NULL = the default stream) - lookm_compress_batch may also use
- *     one stream of the library, ordered against hip_stream by events - and calls do not synchronise
- *     (the measurement aids at the end of this header do, and say so).
+ *     (a hipStream_t passed as void*, NULL = the default stream; lookm_compress_batch_two_streams takes a
+ *     second one) and calls do not synchronise (the measurement aids at the end of this header do, and
+ *     say so).  The library creates no stream; it keeps no state between calls except "kernel attributes
+ *     are set on this device" (see lookm_init).
  *   - The return value reports everything the host can check (negative lookm_status); those checks
  *     run before any kernel is launched and need no GPU.  The one check that needs device data
  *     (budget smaller than the number of protected positions) is reported through `status_out`.
@@ -76,6 +77,14 @@ typedef enum {
 
 /* Library version string, static storage. */
 const char* lookm_version(void);
+
+/*
+ * Optional: sets, once for the current device, the attributes some kernels need (larger dynamic LDS for every
+ * template instance).  Every launching entry point does the same on its first call on a device; a caller that
+ * captures HIP graphs calls this once per device beforehand, so that nothing but launches happens under capture.
+ * Returns LOOKM_OK or LOOKM_ERR_DEVICE.  Thread-safe.
+ */
+int lookm_init(void);
 
 /* Human-readable name of a lookm_status value, static storage. */
 const char* lookm_status_string(int status);
@@ -255,18 +264,27 @@ typedef struct lookm_job {
  * different lengths.  EVERY job is validated before the first launch: on an invalid job nothing is enqueued,
  * the return value is that job's error and *bad_job (if not NULL) its index.  n_jobs = 0 is a no-op.
  *
- * Order and streams.  The result is what running the jobs one after the other in the order given would give.  Jobs
- * that touch disjoint memory need not wait for each other, though: the library alternates such jobs between
- * hip_stream and ONE stream of its own (default priority, created on first use, one per device, kept until the
- * process ends), so that the short latency-bound kernels of one job run under the long kernels of another.  Two jobs
- * are kept in order whenever one writes (workspace, k_out, v_out, kept_idx, scores_out, status_out) what the other
- * reads or writes; give independent prompts their own workspace and outputs to let them overlap, and pass the jobs in
- * the order a prefill produces them (layer 0 of every prompt, then layer 1, ...).  All work of the call starts after
- * the work already enqueued on hip_stream and is complete before anything enqueued on hip_stream afterwards (event
- * fork / join; no host synchronisation).  When hip_stream is being captured into a graph the jobs are simply
- * enqueued in order on hip_stream.  Calls from several host threads are serialised by a lock.
+ * The jobs are enqueued on hip_stream in the order given.
  */
 int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream);
+
+/*
+ * The same on two streams of the caller (both of default priority, on the current device, hip_stream_aux different
+ * from hip_stream, else LOOKM_ERR_INVALID_ARG).  The result is what running the jobs one after the other in the
+ * order given would give.  Jobs that touch disjoint memory need not wait for each other, though: the library
+ * alternates such jobs between the two streams, so that the short latency-bound kernels of one job run under the long
+ * kernels of another.  Two jobs are kept in order whenever one writes (workspace, k_out, v_out, kept_idx, scores_out,
+ * status_out) what the other reads or writes; give independent prompts - or the two halves of one layer's heads -
+ * their own workspace and outputs to let them overlap, and pass the jobs in the order a prefill produces them (layer
+ * 0 of every prompt, then layer 1, ...).  All work of the call starts after the work already enqueued on hip_stream
+ * and is complete before anything enqueued on hip_stream afterwards (event fork / join; no host synchronisation; the
+ * events are created and destroyed inside the call, the library keeps no stream and no event).  Work enqueued on
+ * hip_stream_aux BEFORE the call is not waited for, and work enqueued there afterwards is ordered only after the
+ * jobs that ran on it.  When either stream is being captured into a graph the jobs are simply enqueued in order on
+ * hip_stream.
+ */
+int lookm_compress_batch_two_streams(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream,
+                                     void* hip_stream_aux);
 
 /* ---- the step after the path: one new token attends to the (compressed) cache ------------------------------ */
 
@@ -286,6 +304,22 @@ int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cac
                            lookm_dtype dt, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* ---- measurement aid ------------------------------------------------------------------------------- */
+
+/* Intermediate results that lookm_compress (or a job) leaves in its workspace, for callers that want to inspect
+ * them (the parity tests do): the evicted positions of Eq. 8's complement, and the matching of Eq. 9. */
+typedef enum {
+    LOOKM_WS_EVICTED = 0,   /* int32 [kv_heads, L - budget], ascending positions */
+    LOOKM_WS_ASSIGN = 1,    /* int32 [kv_heads, L - budget], slot of the matched conserved key */
+    LOOKM_WS_SIM = 2        /* float [kv_heads, L - budget], the matching cosine */
+} lookm_workspace_item;
+
+/*
+ * Host helper: byte offset of an intermediate array inside a (256-byte aligned) workspace of the given problem,
+ * valid after the work of a lookm_compress / lookm_compress_lse / job call with the same sizes has completed
+ * (H query heads, kv_heads key / value heads; kv_heads = H without grouped query heads).  Returns (size_t)-1 on
+ * invalid sizes or item.  The arrays hold what the call computed when it merged (merge_mode != NONE, 0 < budget < L).
+ */
+size_t lookm_workspace_offset(int H, int kv_heads, int L, int d, int budget, lookm_dtype dt, lookm_workspace_item item);
 
 /* Kernels of the path, in launch order (Section 3.2: the two score passes and the selection;
  * Section 3.3: key norms, matching, similarity sets, merge + compaction).  For bf16 with d = 128 the key norms are

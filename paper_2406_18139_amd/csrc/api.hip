@@ -70,7 +70,7 @@ template <typename T> T* at(void* base, size_t off) { return reinterpret_cast<T*
 
 // ---- two lanes for independent jobs of a batch -----------------------------------------------------------
 // Jobs that touch disjoint memory do not have to wait for each other: alternating them between the caller's
-// stream and one stream of the library lets the short, latency-bound kernels of one job (selection, set sort,
+// stream and a second stream of the caller lets the short, latency-bound kernels of one job (selection, set sort,
 // folds) and the tail of its long kernels run under the long kernels of the next.  Everything stays ordered
 // after the work already on the caller's stream and before the work the caller enqueues next (fork / join with
 // events); jobs that share a workspace or an output keep their order.
@@ -125,38 +125,19 @@ bool conflict(const JobFootprint& a, const JobFootprint& b)
     return false;
 }
 
-// the library's second stream and its events, one set per device, created on first use and kept until the process
-// ends (default priority, like every stream here)
-struct SideLane {
-    hipStream_t stream = nullptr;
-    std::vector<hipEvent_t> events;
-    size_t used = 0;
-    bool failed = false;
-};
-constexpr int kMaxDevices = 64;
-SideLane g_side[kMaxDevices];
-std::mutex g_side_mutex;
-
-hipEvent_t next_event(SideLane& s)
+// `later` waits for everything enqueued on `earlier` so far.  The event lives until the end of the call that made
+// it (destroying a recorded event only releases it once it has completed).
+bool order_after(std::vector<hipEvent_t>& events, hipStream_t earlier, hipStream_t later)
 {
-    if (s.used == s.events.size()) {
-        hipEvent_t e = nullptr;
-        if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
-        s.events.push_back(e);
-    }
-    return s.events[s.used++];
-}
-
-// `later` waits for everything enqueued on `earlier` so far
-bool order_after(SideLane& s, hipStream_t earlier, hipStream_t later)
-{
-    hipEvent_t e = next_event(s);
-    return e != nullptr && hipEventRecord(e, earlier) == hipSuccess && hipStreamWaitEvent(later, e, 0) == hipSuccess;
+    hipEvent_t e = nullptr;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return false;
+    events.push_back(e);
+    return hipEventRecord(e, earlier) == hipSuccess && hipStreamWaitEvent(later, e, 0) == hipSuccess;
 }
 
 int enqueue_job(const lookm_job& j, hipStream_t st);
 
-int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t main)
+int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t main, hipStream_t aux, bool two_lanes)
 {
     auto serial = [&](int from) {
         for (int i = from; i < n_jobs; ++i) {
@@ -168,31 +149,18 @@ int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t m
         }
         return (int)LOOKM_OK;
     };
-    int dev = 0;
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    // one job, a stream under graph capture (no stream or event is created while a capture is open), or an unknown
-    // device: the plain loop
-    if (n_jobs < 2) return serial(0);
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices ||
-        hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) {
-        (void)hipGetLastError();   // a failed query must not be taken for a failed launch later
+    // one job, no second stream, or a stream under graph capture (no event is created while a capture is open):
+    // the plain loop
+    if (n_jobs < 2 || !two_lanes) return serial(0);
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone, cap2 = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone ||
+        hipStreamIsCapturing(aux, &cap2) != hipSuccess || cap2 != hipStreamCaptureStatusNone)
         return serial(0);
-    }
 
-    std::lock_guard<std::mutex> lock(g_side_mutex);
-    SideLane& side = g_side[dev];
-    if (side.stream == nullptr && !side.failed &&
-        hipStreamCreateWithFlags(&side.stream, hipStreamNonBlocking) != hipSuccess) {
-        side.stream = nullptr;
-        side.failed = true;
-        (void)hipGetLastError();
-    }
-    if (side.stream == nullptr) return serial(0);
-    side.used = 0;
-
-    hipStream_t lane[2] = {main, side.stream};
+    std::vector<hipEvent_t> events;
+    hipStream_t lane[2] = {main, aux};
     // jobs of a lane that the other lane has not been ordered after yet; before the fork only the caller's lane
-    // exists, and the fork itself orders the side lane after all of it
+    // exists, and the fork itself orders the second lane after all of it
     std::vector<JobFootprint> open[2];
     bool forked = false;
     int rc = LOOKM_OK, bad = 0;
@@ -207,37 +175,60 @@ int enqueue_batch(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t m
         int want = i & 1;
         if (hit[0] != hit[1]) want = hit[0] ? 0 : 1;
         const int other = 1 - want;
-        if (want == 1 && !forked) {           // the side lane starts after the work already on the caller's stream
-            if (!order_after(side, main, side.stream)) { rc = LOOKM_ERR_DEVICE; break; }
+        if (want == 1 && !forked) {           // the second lane starts after the work already on the first
+            if (!order_after(events, main, aux)) { rc = LOOKM_ERR_DEVICE; break; }
             forked = true;
             open[0].clear();
         }
         if (hit[other]) {                     // depends on both lanes: wait for the other one here
-            if (!order_after(side, lane[other], lane[want])) { rc = LOOKM_ERR_DEVICE; break; }
+            if (!order_after(events, lane[other], lane[want])) { rc = LOOKM_ERR_DEVICE; break; }
             open[other].clear();
         }
         rc = enqueue_job(jobs[i], lane[want]);
         open[want].push_back(f);
         if (open[want].size() >= 64) {        // keep the lists short: let the other lane catch up with this one
             if (forked) {
-                if (!order_after(side, lane[want], lane[other])) { rc = LOOKM_ERR_DEVICE; break; }
+                if (!order_after(events, lane[want], lane[other])) { rc = LOOKM_ERR_DEVICE; break; }
                 open[want].clear();
             } else {
                 open[want].erase(open[want].begin());
             }
         }
     }
-    // join: whatever the caller enqueues next comes after both lanes
-    if (forked && !order_after(side, side.stream, main) && rc == LOOKM_OK) rc = LOOKM_ERR_DEVICE;
+    // join: whatever the caller enqueues next on hip_stream comes after both lanes
+    if (forked && !order_after(events, aux, main) && rc == LOOKM_OK) rc = LOOKM_ERR_DEVICE;
+    for (hipEvent_t e : events) (void)hipEventDestroy(e);
     if (rc != LOOKM_OK && bad_job) *bad_job = bad;
     return rc;
 }
 
+// kernel attributes, once per device (see common.h)
+constexpr int kMaxDevices = 64;
+std::mutex g_ready_mutex;
+bool g_ready[kMaxDevices];
+
 }  // namespace
+
+namespace lookm_host {
+int ensure_device_ready()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LOOKM_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_ready_mutex);
+    if (g_ready[dev]) return LOOKM_OK;
+    if (set_attributes_score_generic() != LOOKM_OK || set_attributes_nearest_generic() != LOOKM_OK ||
+        set_attributes_merge() != LOOKM_OK)
+        return LOOKM_ERR_DEVICE;
+    g_ready[dev] = true;
+    return LOOKM_OK;
+}
+}  // namespace lookm_host
 
 extern "C" {
 
-const char* lookm_version(void) { return "lookm 0.1 (gfx950)"; }
+const char* lookm_version(void) { return "lookm 0.2 (gfx950)"; }
+
+int lookm_init(void) { return lookm_host::ensure_device_ready(); }
 
 const char* lookm_status_string(int status)
 {
@@ -268,6 +259,19 @@ size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt)
     return make_layout(H, H, L, d, (int)dt, budget).total;
 }
 
+size_t lookm_workspace_offset(int H, int kv_heads, int L, int d, int budget, lookm_dtype dt, lookm_workspace_item item)
+{
+    if (check_shape(H, L, d, (int)dt) != LOOKM_OK || budget < 0 || budget > L || kv_heads <= 0 || H % kv_heads != 0)
+        return (size_t)-1;
+    const Layout w = make_layout(H, kv_heads, L, d, (int)dt, budget);
+    switch (item) {
+        case LOOKM_WS_EVICTED: return w.evicted;
+        case LOOKM_WS_ASSIGN: return w.assign;
+        case LOOKM_WS_SIM: return w.sim;
+        default: return (size_t)-1;
+    }
+}
+
 static int scores_impl(const void* q, const void* k, const float* row_lse, int H, int kv_heads, int L, int d,
                        lookm_dtype dt, int window, float* scores_out, void* workspace, size_t workspace_bytes,
                        void* hip_stream)
@@ -281,6 +285,7 @@ static int scores_impl(const void* q, const void* k, const float* row_lse, int H
     rc = check_workspace(workspace, workspace_bytes, H, kv_heads, L, d, (int)dt, 0);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, kv_heads, L, d, (int)dt, 0);
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return lookm_host::launch_scores(q, k, H, kv_heads, L, d, dt, window ? L - window : 0, at<float>(workspace, w.lse),
                                      row_lse, scores_out, nullptr, at<float>(workspace, w.partials),
                                      (hipStream_t)hip_stream);
@@ -324,6 +329,7 @@ int lookm_select_rule_(const float* scores, const uint8_t* modality_mask, int H,
     if (rc != LOOKM_OK) return rc;
     // an empty list (budget 0, or budget L) may be passed as NULL
     if ((budget > 0 && !kept_idx) || (budget < L && !evicted_idx)) return LOOKM_ERR_INVALID_ARG;
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return lookm_host::launch_select(scores, modality_mask, H, L, budget, recent_window, (int)rule, kept_idx,
                                      evicted_idx, status_out, (hipStream_t)hip_stream);
 }
@@ -360,6 +366,7 @@ int lookm_nearest(const void* k, const int32_t* kept_idx, const int32_t* evicted
     rc = check_workspace(workspace, workspace_bytes, H, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, H, L, d, (int)dt, budget);
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return lookm_host::launch_nearest(k, kept_idx, evicted_idx, H, L, d, dt, budget, at<float>(workspace, w.rnorm),
                                       false, assign, sim, at<void>(workspace, w.partials), (hipStream_t)hip_stream);
 }
@@ -380,6 +387,7 @@ int lookm_merge(const void* k, const void* v, const int32_t* kept_idx, const int
     rc = check_workspace(workspace, workspace_bytes, H, H, L, d, (int)dt, budget);
     if (rc != LOOKM_OK) return rc;
     const Layout w = make_layout(H, H, L, d, (int)dt, budget);
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return lookm_host::launch_merge(k, v, kept_idx, evicted_idx, assign, sim, H, L, d, dt, budget, (int)merge_mode,
                                     at<int32_t>(workspace, w.plan), at<int32_t>(workspace, w.member_pos),
                                     at<float>(workspace, w.member_w), k_out, v_out, (hipStream_t)hip_stream);
@@ -458,8 +466,9 @@ static int compress_impl(const void* q, const void* k, const void* v, const uint
     j.score_window = 0; j.kv_heads = 0;
     j.k_out = k_out; j.v_out = v_out; j.kept_idx = kept_idx; j.scores_out = scores_out; j.status_out = status_out;
     j.workspace = workspace; j.workspace_bytes = workspace_bytes;
-    const int rc = validate_job(j);
+    int rc = validate_job(j);
     if (rc != LOOKM_OK) return rc;
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return enqueue_job(j, (hipStream_t)hip_stream);
 }
 
@@ -482,7 +491,7 @@ int lookm_compress_lse(const void* q, const void* k, const void* v, const uint8_
                          kept_idx, scores_out, status_out, workspace, workspace_bytes, hip_stream);
 }
 
-int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream)
+static int batch_impl(const lookm_job* jobs, int n_jobs, int* bad_job, hipStream_t main, hipStream_t aux, bool two_lanes)
 {
     if (n_jobs < 0 || (n_jobs > 0 && !jobs)) return LOOKM_ERR_INVALID_ARG;
     for (int i = 0; i < n_jobs; ++i) {
@@ -492,8 +501,22 @@ int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* 
             return rc;
         }
     }
-    const int rc = enqueue_batch(jobs, n_jobs, bad_job, (hipStream_t)hip_stream);
-    return rc;
+    if (n_jobs == 0) return LOOKM_OK;
+    const int rc = lookm_host::ensure_device_ready();
+    if (rc != LOOKM_OK) return rc;
+    return enqueue_batch(jobs, n_jobs, bad_job, main, aux, two_lanes);
+}
+
+int lookm_compress_batch(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream)
+{
+    return batch_impl(jobs, n_jobs, bad_job, (hipStream_t)hip_stream, nullptr, false);
+}
+
+int lookm_compress_batch_two_streams(const lookm_job* jobs, int n_jobs, int* bad_job, void* hip_stream,
+                                     void* hip_stream_aux)
+{
+    if (hip_stream_aux == hip_stream) return LOOKM_ERR_INVALID_ARG;
+    return batch_impl(jobs, n_jobs, bad_job, (hipStream_t)hip_stream, (hipStream_t)hip_stream_aux, true);
 }
 
 size_t lookm_decode_workspace_bytes(int H, int d)
@@ -514,6 +537,8 @@ int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cac
     if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
         workspace_bytes < lookm_host::decode_scratch_bytes(H, d))
         return LOOKM_ERR_WORKSPACE;
+    const int rdy = lookm_host::ensure_device_ready();
+    if (rdy != LOOKM_OK) return rdy;
     return lookm_host::launch_decode(q, k_cache, v_cache, H, rows, S, d, dt, out, static_cast<float*>(workspace),
                                      (hipStream_t)hip_stream);
 }
@@ -523,10 +548,14 @@ int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, voi
     if (!job || reps <= 0 || kernel_ms_host == nullptr) return LOOKM_ERR_INVALID_ARG;
     int rc = validate_job(*job);
     if (rc != LOOKM_OK) return rc;
+    if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     lookm_host::KernelTimer timer;
     timer.st = (hipStream_t)hip_stream;
     for (int i = 0; i <= LOOKM_N_KERNELS; ++i)
-        if (hipEventCreate(&timer.ev[i]) != hipSuccess) return LOOKM_ERR_DEVICE;
+        if (hipEventCreate(&timer.ev[i]) != hipSuccess) {
+            while (--i >= 0) (void)hipEventDestroy(timer.ev[i]);
+            return LOOKM_ERR_DEVICE;
+        }
     double sum[LOOKM_N_KERNELS] = {0};
     for (int r = 0; r < reps && rc == LOOKM_OK; ++r) {
         // a kernel that is skipped for these sizes leaves its event at this early time (handled below); the

@@ -100,6 +100,27 @@ size_t decode_scratch_bytes(int H, int d);
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }
 
+// A launcher's verdict on its own launches: an error that is pending on this host thread after them and was not
+// pending before.  Nothing is cleared, so an error that an unrelated earlier call left behind is neither taken
+// for a failed launch nor hidden from the caller.
+struct LaunchCheck {
+    hipError_t before;
+    LaunchCheck() : before(hipPeekAtLastError()) {}
+    int status() const
+    {
+        const hipError_t after = hipPeekAtLastError();
+        return (after == hipSuccess || after == before) ? LOOKM_OK : LOOKM_ERR_DEVICE;
+    }
+};
+
+// Kernels that need more dynamic LDS than the default limit get the attribute set for EVERY template instance,
+// once per device, by ensure_device_ready() (api.hip) - never lazily per instance, so that a shape met for the
+// first time inside a stream capture finds its kernel ready.  Each returns LOOKM_OK or LOOKM_ERR_DEVICE.
+int set_attributes_score_generic();
+int set_attributes_nearest_generic();
+int set_attributes_merge();
+int ensure_device_ready();
+
 // Per-kernel timing for lookm_compress_profile: when a timer is installed, every launcher records an
 // event after each kernel it enqueues (ids follow the LOOKM_K_* order of the header).
 struct KernelTimer {

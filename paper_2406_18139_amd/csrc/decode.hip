@@ -181,6 +181,7 @@ template <typename T>
 static int launch_decode_t(const T* q, const T* k, const T* v, int H, int rows, int S, int d, T* out, float* part,
                            hipStream_t st)
 {
+    const LaunchCheck check;
     int G = 1;
     while (G * 8 < d) G <<= 1;
     const int NG = lookm::DC_THREADS / G, nsplit = decode_pieces(H, S, G);
@@ -192,7 +193,7 @@ static int launch_decode_t(const T* q, const T* k, const T* v, int H, int rows, 
                        G, nsplit, scale2, part);
     hipLaunchKernelGGL(lookm::k_decode_merge<T>, dim3(H), dim3(lookm::DC_MERGE_THREADS), 0, st, part, d, dpad, nsplit,
                        out);
-    return hip_ok(hipGetLastError());
+    return check.status();
 }
 
 int launch_decode(const void* q, const void* k, const void* v, int H, int rows, int S, int d, lookm_dtype dt, void* out,

@@ -347,13 +347,6 @@ static int launch_bucket(const int32_t* assign, const int32_t* evicted, const fl
                          hipStream_t st)
 {
     const size_t lds = (size_t)lookm::BK_WAVES * (S * sizeof(int) + 64 * IPT * sizeof(unsigned short));
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)lookm::k_bucket<IPT>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                lookm::BK_WAVES * (lookm::BK_MAX_SEG * 4 + 64 * IPT * 2)) != hipSuccess)
-            return LOOKM_ERR_DEVICE;
-        attr_done = true;
-    }
     int nbits = 1;
     while ((1 << nbits) < S) ++nbits;
     hipLaunchKernelGGL(lookm::k_bucket<IPT>, dim3(NS, H), dim3(lookm::BK_THREADS), lds, st, assign, evicted, sim, kept,
@@ -367,6 +360,7 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
 {
     const int B = budget, Le = L - B;
     if (B == 0) return LOOKM_OK;
+    const LaunchCheck check;
     if (Le == 0) mode = LOOKM_MERGE_NONE;
     int4* plan = reinterpret_cast<int4*>(plan_words);
     int S, NS;
@@ -394,7 +388,19 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
         launch_merge_t((const float*)k, (const float*)v, kept, plan, member_pos, member_w, H, L, d, B, mode, S, NS,
                        (float*)k_out, (float*)v_out, st);
     mark(LOOKM_K_MERGE);
-    return hip_ok(hipGetLastError());
+    return check.status();
+}
+
+template <int IPT> static bool bucket_attribute()
+{
+    return hipFuncSetAttribute((const void*)lookm::k_bucket<IPT>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               lookm::BK_WAVES * (lookm::BK_MAX_SEG * 4 + 64 * IPT * 2)) == hipSuccess;
+}
+
+int set_attributes_merge()
+{
+    return (bucket_attribute<4>() && bucket_attribute<8>() && bucket_attribute<16>() && bucket_attribute<32>())
+               ? LOOKM_OK : LOOKM_ERR_DEVICE;
 }
 
 }  // namespace lookm_host

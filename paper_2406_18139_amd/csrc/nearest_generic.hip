@@ -131,6 +131,7 @@ static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evic
 {
     const int Le = L - budget;
     if (Le == 0) return LOOKM_OK;
+    const LaunchCheck check;
     const size_t rows = (size_t)H * L;
     if (!rnorm_ready)
         hipLaunchKernelGGL(lookm::k_rnorm<T>, dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, st, k, rows, d, rnorm);
@@ -138,18 +139,20 @@ static int launch_nearest_t(const T* k, const int32_t* kept, const int32_t* evic
     if (mfma) return launch_nearest_mfma(k, kept, evicted, H, L, budget, rnorm, assign, sim, scratch, st);
     size_t lds = (size_t)2 * d * lookm::NT_TS * sizeof(float);
     if (lds < 8192) lds = 8192;
-    static bool attr_done = false;
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)lookm::k_nearest_generic<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                150 * 1024) != hipSuccess)
-            return LOOKM_ERR_DEVICE;
-        attr_done = true;
-    }
     dim3 grid((Le + lookm::NT_TS - 1) / lookm::NT_TS, H);
     hipLaunchKernelGGL(lookm::k_nearest_generic<T>, grid, dim3(256), lds, st, k, rnorm, kept, evicted, L, d, budget,
                        Le, assign, sim);
     mark(LOOKM_K_NEAREST);
-    return hip_ok(hipGetLastError());
+    return check.status();
+}
+
+int set_attributes_nearest_generic()
+{
+    const bool ok = hipFuncSetAttribute((const void*)lookm::k_nearest_generic<float>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) == hipSuccess &&
+                    hipFuncSetAttribute((const void*)lookm::k_nearest_generic<lookm::bf16_t>,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024) == hipSuccess;
+    return ok ? LOOKM_OK : LOOKM_ERR_DEVICE;
 }
 
 size_t nearest_scratch_bytes(int H, int L, int d, lookm_dtype dt, int budget)

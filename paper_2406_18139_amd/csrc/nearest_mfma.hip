@@ -6,13 +6,23 @@
 // is in-lane; the lane pair (lane, lane^32) is merged once after the loop.  The similarity matrix never
 // exists in memory.
 //
-// Argmax without per-element compare/select chains: with y = (k_e.k_c)/||k_c|| = cos * ||k_e||, the value
-// t = ||k_e|| + y lies in [0, 2||k_e||], so its float bits order like signed integers (a t that rounding
-// pushed just below 0 is a negative integer and simply loses; ||k_e|| > 0 is common to the whole row);
-// the low 4 mantissa bits of each entry are replaced by 15 - r (r = entry number inside the 32x32
-// block), and one v_max3_i32 tree per block yields both the block maximum and where it sits.  Candidates are therefore compared at 20 mantissa bits (<= 1.9e-6 absolute); equal
-// keys still resolve to the lower slot exactly.  Across blocks, chunks and the lane pair the order is
-// (truncated value descending, slot ascending).  The `sim` output is decoded from the winning key.
+// Argmax without per-element compare/select chains: y = (k_e.k_c)/||k_c|| = cos * ||k_e|| orders the conserved
+// keys of one evicted key like the cosine does, and the float bits of a positive y order like signed integers
+// (every positive y beats every negative one; a row whose best y is not positive is decided by the exact pass
+// below).  The low 4 mantissa bits of each entry are replaced by 15 - r (r = entry number inside the 32x32 block),
+// and one tree of v_max3 / v_med3 per block yields the block's largest key - value and place at once - and its
+// second largest.  Candidates are therefore compared at 20 mantissa bits (one unit = 16 ulp, at most 1.9e-6
+// relative); equal keys still resolve to the lower slot exactly.  Across blocks, chunks and the lane pair the
+// order is (truncated value descending, slot ascending), and the runner-up's key is carried along.
+//
+// Exact decisions.  The matrix-core value of y differs from the true one by well under one unit (fp32
+// accumulation of exact products, one fp32 inverse norm, one product: a few ulp), so the true maximum can only
+// be a key whose truncated value lies within NEAR_UNITS units of the best one.  k_nearest_fold therefore takes
+// the matrix-core choice only where the runner-up is farther away than that; every other evicted key (a few per
+// ten thousand) is decided again by an exact pass: all conserved keys within a wide band of the best are
+// evaluated in binary64 with a fixed arithmetic contract - sequential sums over k = 0..d-1 of products that are
+// exact in binary64, binary64 square roots, one product, one division, first maximum in slot order - which is a
+// definition, not an approximation, so any implementation of the same contract takes the same decision.
 //
 // The conserved axis is cut into chunks (one workgroup per (evicted strip, chunk)) chosen so that the
 // number of workgroups fills the resident slots evenly; enumeration is chunk-major and XCD-affine as in
@@ -30,11 +40,35 @@ typedef __attribute__((ext_vector_type(16))) float nf32x16;
 constexpr int ND = 128, NBS = 256, NBX = 64, NXROW = 128;   // LDS rows are unpadded, chunks swizzled
 static_assert(NBX == 64, "the norms of a tile are staged by wave 0, one row per lane");
 
-// partial result of one (evicted strip, chunk): key = float bits of t >> 4, slot
+constexpr int NEAR_UNITS = 2;   // a runner-up within this many units of the best truncated value: decided exactly
+
+// partial result of one (evicted strip, chunk): truncated value (float bits of y >> 4) and slot of the best
+// conserved key, truncated value of the runner-up
 struct NearestPartial {
     int32_t key;
     int32_t slot;
+    int32_t second;
 };
+
+__device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
+__device__ __forceinline__ int imed3(int a, int b, int c) { return max(min(a, b), min(max(a, b), c)); }
+
+// largest and second largest of 16 distinct keys in 20 three-input operations: five triples give their maximum
+// and their median; the largest key is the maximum of the maxima, and the runner-up is either the median of the
+// triple (or of the group of maxima) that holds the largest key, or the best of the rest - all of which are below
+// the largest key, so their maximum is the runner-up whichever group won.
+__device__ __forceinline__ void top2_of_16(const int (&u)[16], int& first, int& second)
+{
+    const int m0 = imax3(u[0], u[1], u[2]), d0 = imed3(u[0], u[1], u[2]);
+    const int m1 = imax3(u[3], u[4], u[5]), d1 = imed3(u[3], u[4], u[5]);
+    const int m2 = imax3(u[6], u[7], u[8]), d2 = imed3(u[6], u[7], u[8]);
+    const int m3 = imax3(u[9], u[10], u[11]), d3 = imed3(u[9], u[10], u[11]);
+    const int m4 = imax3(u[12], u[13], u[14]), d4 = imed3(u[12], u[13], u[14]);
+    const int a1 = imax3(m0, m1, m2), a2 = imed3(m0, m1, m2);
+    const int b1 = imax3(m3, m4, u[15]), b2 = imed3(m3, m4, u[15]);
+    first = max(a1, b1);
+    second = max(imax3(d0, d1, d2), imax3(d3, d4, imax3(min(a1, b1), a2, b2)));
+}
 
 __global__ void __launch_bounds__(256, 3)
 k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
@@ -121,24 +155,26 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         LOOKM_ROW_TO_LDS(o3, 3, buf);                                                         \
         if (wave == 0) stage_r = rnorm[ridx];                                                 \
     } while (0)
-#define LOOKM_STORE_TILE(rbuf)                                 \
-    do {                                                       \
-        if (wave == 0) (rbuf)[tid] = stage_r;                  \
+    // x0: first slot of the tile that was loaded; slots past the end of the conserved list get inverse norm 0, so
+    // their y is zero and they lose to every positive value (a row with no positive value is decided exactly)
+#define LOOKM_STORE_TILE(rbuf, x0)                                       \
+    do {                                                                 \
+        if (wave == 0) (rbuf)[tid] = ((x0) + tid < B) ? stage_r : 0.f;   \
     } while (0)
 
     // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks); scalars, not an array
     const int fo0 = ((0 + half) ^ (n & 7)) * 8, fo1 = ((2 + half) ^ (n & 7)) * 8, fo2 = ((4 + half) ^ (n & 7)) * 8,
               fo3 = ((6 + half) ^ (n & 7)) * 8;
 
-    // per stationary row of this lane; the initial state decodes to slot 0 with t = 0 (= cosine -1)
-    int bhi[2] = {0, 0};            // best truncated key (>> 4)
-    int bkey[2] = {15, 15};         // its full key (low 4 bits: 15 - entry number)
-    int bxb[2] = {0, 0};            // slot of entry 0 of the block it came from
+    // per stationary row of this lane; the initial state is below every key and decodes to slot 0
+    constexpr int KEY_MIN = (int)0x80000000;
+    int bkey[2] = {KEY_MIN | 15, KEY_MIN | 15};   // best key (low 4 bits: 15 - entry number)
+    int bsec[2] = {KEY_MIN, KEY_MIN};             // runner-up key
+    int bxb[2] = {0, 0};                          // slot of entry 0 of the block the best key came from
 
     LOOKM_LOAD_INDEX(x_begin);           // in flight together with the evicted positions
 
     nbf16x8 sf[2][8];
-    float off[2];    // ||k_e|| of this lane's two evicted keys (0 for a zero key)
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
         const int pos = cb ? pos1 : pos0;
@@ -147,12 +183,9 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         for (int ks = 0; ks < 8; ++ks)
             sf[cb][ks] = __builtin_bit_cast(nbf16x8, *reinterpret_cast<const uint4*>(row + ks * 16 + half * 8));
     }
-    const float rne0 = rnorm[pos0], rne1 = rnorm[pos1];
     LOOKM_LOAD_TILE(xs0);
     LOOKM_LOAD_INDEX(x_begin + NBX);     // clamped, so always in range
-    LOOKM_STORE_TILE(xr0);
-    off[0] = (rne0 > 0.f) ? 1.0f / rne0 : 0.f;
-    off[1] = (rne1 > 0.f) ? 1.0f / rne1 : 0.f;
+    LOOKM_STORE_TILE(xr0, x_begin);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
@@ -197,23 +230,20 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const int r = 4 * g + i;
-                        // ||k_e|| + (k_e.k_c) * rnorm_c (a zero evicted key gives 0 everywhere: slot 0 wins)
-                        const float t = fmaf(acc[cb][r], rn[i], off[cb]);
-                        u[r] = (int)((__float_as_uint(t) & 0xfffffff0u) | (uint32_t)(15 - r));
+                        // y = (k_e.k_c) * rnorm_c (a zero evicted key gives 0 everywhere: decided exactly, slot 0)
+                        const float y = acc[cb][r] * rn[i];
+                        u[r] = (int)((__float_as_uint(y) & 0xfffffff0u) | (uint32_t)(15 - r));
                     }
                 }
-                int bm = max(max(u[0], u[1]), u[2]);
-#pragma unroll
-                for (int r = 3; r < 15; r += 2) bm = max(max(bm, u[r]), u[r + 1]);
-                bm = max(bm, u[15]);
-                const int hi = bm >> 4;
-                const bool better = hi > bhi[cb];   // strict: an equal value in a later block loses
-                bhi[cb] = better ? hi : bhi[cb];
+                int bm, bs2;
+                top2_of_16(u, bm, bs2);
+                const bool better = (bm >> 4) > (bkey[cb] >> 4);   // strict: an equal value in a later block loses
+                bsec[cb] = imax3(min(bkey[cb], bm), bsec[cb], bs2);
                 bkey[cb] = better ? bm : bkey[cb];
                 bxb[cb] = better ? xb : bxb[cb];
             }
         }
-        if (it + 1 < n_it) LOOKM_STORE_TILE(nxt_r);
+        if (it + 1 < n_it) LOOKM_STORE_TILE(nxt_r, x0 + NBX);
         __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): the next tile's direct-to-LDS loads have landed
         __syncthreads();
     };
@@ -231,41 +261,157 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     for (int cb = 0; cb < 2; ++cb) {
         const int r = 15 - (bkey[cb] & 15);
         int slot = bxb[cb] + 8 * (r >> 2) + (r & 3);
-        int hi = bhi[cb];
-        const int ohi = __shfl_xor(hi, 32);
-        const int oslot = __shfl_xor(slot, 32);
-        if (ohi > hi || (ohi == hi && oslot < slot)) { hi = ohi; slot = oslot; }
+        int hi = bkey[cb] >> 4, sec = bsec[cb] >> 4;
+        const int ohi = __shfl_xor(hi, 32), oslot = __shfl_xor(slot, 32), osec = __shfl_xor(sec, 32);
+        const bool other = ohi > hi || (ohi == hi && oslot < slot);
+        sec = imax3(other ? hi : ohi, sec, osec);       // the loser of the pair is a runner-up candidate
+        if (other) { hi = ohi; slot = oslot; }
         if (half == 0) {
             NearestPartial p;
             p.key = hi;
             p.slot = slot;
+            p.second = sec;
             out[wave * 64 + cb * 32 + n] = p;
         }
     }
 }
 
-// Folds the chunks of every evicted key (value descending, slot ascending): assign[h, e] = slot and
-// sim[h, e] = cosine, decoded from the winning key at the centre of its truncation interval
-// (|error| <= 1e-6).  One thread per evicted key.
-__global__ void __launch_bounds__(256)
-k_nearest_fold(const float* __restrict__ rnorm, const int32_t* __restrict__ evicted, int L, int B, int Le,
-               int n_strips, int n_chunks, const NearestPartial* __restrict__ part, int32_t* __restrict__ assign,
-               float* __restrict__ sim)
+// cosine of two keys under the exact contract: sequential binary64 sums over k = 0..127 (every product of two
+// bf16 values is exact in binary64, so a fused multiply-add gives the same bits as multiply-then-add), binary64
+// square roots (correctly rounded), one product, one division; 0 when either norm vanishes.
+__device__ __forceinline__ double cosine_exact(const bf16_t* __restrict__ a, const bf16_t* __restrict__ b)
 {
-    const int h = blockIdx.y;
-    const int ev = blockIdx.x * 256 + threadIdx.x;
-    if (ev >= Le) return;
-    const int strip = ev / NBS, r = ev % NBS;
-    int bk = -1, bs = 0x7fffffff;
-    for (int c = 0; c < n_chunks; ++c) {
-        const NearestPartial p = part[(((size_t)h * n_chunks + c) * n_strips + strip) * NBS + r];
-        if (p.key > bk || (p.key == bk && p.slot < bs)) { bk = p.key; bs = p.slot; }
+    double na = 0.0, nb = 0.0, ab = 0.0;
+#pragma unroll 1
+    for (int c0 = 0; c0 < ND; c0 += 8) {
+        float x[8], y[8];
+        load8(a + c0, x);
+        load8(b + c0, y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const double xa = (double)x[i], yb = (double)y[i];
+            na = fma(xa, xa, na);
+            nb = fma(yb, yb, nb);
+            ab = fma(xa, yb, ab);
+        }
     }
-    const float rne = rnorm[(size_t)h * L + evicted[(size_t)h * Le + ev]];
-    const float off = (rne > 0.f) ? 1.0f / rne : 0.f;
-    const float t = __uint_as_float(((uint32_t)max(bk, 0) << 4) | 8u);     // ||k_e|| + (k_e.k_c) * rnorm_c
-    assign[(size_t)h * Le + ev] = min(max(bs, 0), B - 1);
-    sim[(size_t)h * Le + ev] = (rne > 0.f) ? (t - off) * rne : 0.f;
+    if (na == 0.0 || nb == 0.0) return 0.0;
+    return ab / (sqrt(na) * sqrt(nb));
+}
+
+constexpr int NF_THREADS = 256;
+constexpr int NF_CAND = 1024;     // capacity of the candidate list of the exact pass
+
+// Folds the chunks of every evicted key (value descending, slot ascending) and carries the runner-up along:
+// one thread per evicted key.  Where the runner-up is more than NEAR_UNITS units below the best value the
+// matrix-core choice stands: assign[h, e] = its slot, sim[h, e] = the cosine decoded from the centre of the
+// key's truncation interval (|error| < 1.2e-6).  Every other key of the workgroup is decided by the exact pass:
+// 16 lanes per conserved key recompute y in fp32 (coalesced row reads) and list the slots within a wide band
+// (3e-5 relative) below the best value - or all slots when the best value is not positive - and the listed
+// slots are evaluated with cosine_exact; the first maximum in slot order wins and its cosine is returned.
+__global__ void __launch_bounds__(NF_THREADS)
+k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
+               const int32_t* __restrict__ evicted, int L, int B, int Le, int n_strips, int n_chunks,
+               const NearestPartial* __restrict__ part, int32_t* __restrict__ assign, float* __restrict__ sim)
+{
+    __shared__ int todo[NF_THREADS];          // evicted-list indices that need the exact pass
+    __shared__ float todo_y[NF_THREADS];      // their best matrix-core value (<= 0: no band, every slot is listed)
+    __shared__ int cand[NF_CAND];
+    __shared__ double red_s[NF_THREADS];
+    __shared__ int red_r[NF_THREADS];
+    __shared__ int n_todo, n_cand;
+    const int h = blockIdx.y, tid = threadIdx.x;
+    const int ev = blockIdx.x * NF_THREADS + tid;
+    k += (size_t)h * L * ND;
+    rnorm += (size_t)h * L;
+    kept += (size_t)h * B;
+    evicted += (size_t)h * Le;
+    assign += (size_t)h * Le;
+    sim += (size_t)h * Le;
+    if (tid == 0) n_todo = 0;
+    __syncthreads();
+    if (ev < Le) {
+        const int strip = ev / NBS, r = ev % NBS;
+        int bk = (int)0x80000000, bs = 0x7fffffff, sec = (int)0x80000000;
+        for (int c = 0; c < n_chunks; ++c) {
+            const NearestPartial p = part[(((size_t)h * n_chunks + c) * n_strips + strip) * NBS + r];
+            const bool better = p.key > bk || (p.key == bk && p.slot < bs);
+            sec = imax3(better ? bk : p.key, sec, p.second);
+            if (better) { bk = p.key; bs = p.slot; }
+        }
+        const float y = __uint_as_float(((uint32_t)bk << 4) | 8u);     // (k_e.k_c) * rnorm_c, centre of the interval
+        // bk <= 0: the best value is zero or negative (integer order is not float order there)
+        if (bk <= 0 || sec >= bk - NEAR_UNITS) {
+            const int i = atomicAdd(&n_todo, 1);     // the order of this list decides no result
+            todo[i] = ev;
+            todo_y[i] = (bk > 0) ? y : 0.f;
+        } else {
+            assign[ev] = min(max(bs, 0), B - 1);
+            sim[ev] = y * rnorm[evicted[ev]];
+        }
+    }
+    __syncthreads();
+    const int nt = n_todo;
+    const int grp = tid >> 4, c0 = (tid & 15) * 8;
+    for (int t = 0; t < nt; ++t) {
+        const int e = todo[t];
+        const float ybest = todo_y[t];
+        const bf16_t* ke = k + (size_t)evicted[e] * ND;
+        if (tid == 0) n_cand = 0;
+        __syncthreads();
+        if (ybest > 0.f) {
+            float xe[8];
+            load8(ke + c0, xe);
+            const float bound = ybest * (1.0f - 3.0e-5f);
+            for (int r0 = 0; r0 < B; r0 += NF_THREADS / 16) {
+                const int r = min(r0 + grp, B - 1);
+                const int pos = kept[r];
+                float xc[8];
+                load8(k + (size_t)pos * ND + c0, xc);
+                float dot = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dot = fmaf(xe[i], xc[i], dot);
+                dot += __shfl_xor(dot, 1);
+                dot += __shfl_xor(dot, 2);
+                dot += __shfl_xor(dot, 4);
+                dot += __shfl_xor(dot, 8);
+                if ((tid & 15) == 0 && r0 + grp < B && dot * rnorm[pos] >= bound) {
+                    const int i = atomicAdd(&n_cand, 1);
+                    if (i < NF_CAND) cand[i] = r;
+                }
+            }
+        }
+        __syncthreads();
+        const int nc = n_cand;
+        const bool all = !(ybest > 0.f) || nc > NF_CAND || nc == 0;      // no band, or more candidates than the list holds
+        const int count = all ? B : nc;
+        double best_s = 0.0;
+        int best_r = 0x7fffffff;
+        for (int i = tid; i < count; i += NF_THREADS) {
+            const int r = all ? i : cand[i];
+            const double s = cosine_exact(ke, k + (size_t)kept[r] * ND);
+            if (best_r == 0x7fffffff || s > best_s || (s == best_s && r < best_r)) { best_s = s; best_r = r; }
+        }
+        red_s[tid] = best_s;
+        red_r[tid] = best_r;
+        __syncthreads();
+        for (int off = NF_THREADS / 2; off > 0; off >>= 1) {
+            if (tid < off) {
+                const double s2 = red_s[tid + off];
+                const int r2 = red_r[tid + off];
+                if (r2 != 0x7fffffff && (red_r[tid] == 0x7fffffff || s2 > red_s[tid] || (s2 == red_s[tid] && r2 < red_r[tid]))) {
+                    red_s[tid] = s2;
+                    red_r[tid] = r2;
+                }
+            }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            assign[e] = (red_r[0] == 0x7fffffff) ? 0 : red_r[0];
+            sim[e] = (float)red_s[0];
+        }
+        __syncthreads();
+    }
 }
 
 }  // namespace lookm
@@ -298,6 +444,7 @@ size_t nearest_mfma_scratch_bytes(int H, int L, int B)
 int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int budget,
                         const float* rnorm, int32_t* assign, float* sim, void* scratch, hipStream_t st)
 {
+    const LaunchCheck check;
     const int B = budget, Le = L - B;
     const int strips = (Le + lookm::NBS - 1) / lookm::NBS, tiles = (B + lookm::NBX - 1) / lookm::NBX;
     const int nc = nearest_chunks(H, Le, B);
@@ -311,10 +458,11 @@ int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evict
     hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3(grid), dim3(256), 0, st, (const lookm::bf16_t*)k, rnorm, kept,
                        evicted, H, L, B, Le, strips, n_chunks, CT, part);
     mark(LOOKM_K_NEAREST);
-    hipLaunchKernelGGL(lookm::k_nearest_fold, dim3((Le + 255) / 256, H), dim3(256), 0, st, rnorm, evicted, L, B, Le,
-                       strips, n_chunks, part, assign, sim);
+    hipLaunchKernelGGL(lookm::k_nearest_fold, dim3((Le + lookm::NF_THREADS - 1) / lookm::NF_THREADS, H),
+                       dim3(lookm::NF_THREADS), 0, st, (const lookm::bf16_t*)k, rnorm, kept, evicted, L, B, Le, strips,
+                       n_chunks, part, assign, sim);
     mark(LOOKM_K_NEAREST_FOLD);
-    return hip_ok(hipGetLastError());
+    return check.status();
 }
 
 }  // namespace lookm_host

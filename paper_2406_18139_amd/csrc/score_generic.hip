@@ -174,15 +174,7 @@ static int launch_scores_generic(const T* q, const T* k, int H, int kv_heads, in
     if (lds < 8192) lds = 8192;   // the final cross-thread combine reuses the tile buffers
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
     dim3 grid(nb, H), block(256);
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e1 = hipFuncSetAttribute((const void*)lookm::k_score_lse_generic<T>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        hipError_t e2 = hipFuncSetAttribute((const void*)lookm::k_score_colsum_generic<T>,
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-        if (e1 != hipSuccess || e2 != hipSuccess) return LOOKM_ERR_DEVICE;
-        attr_done = true;
-    }
+    const LaunchCheck check;
     if (!lse_in) {
         hipLaunchKernelGGL(lookm::k_score_lse_generic<T>, grid, block, lds, st, q, k, group, L, R0, d, scale2, lse);
         mark(LOOKM_K_SCORE_LSE);
@@ -191,7 +183,20 @@ static int launch_scores_generic(const T* q, const T* k, int H, int kv_heads, in
     hipLaunchKernelGGL(lookm::k_score_colsum_generic<T>, dim3(nb, kv_heads), block, lds, st, q, k, group, L, R0, d, scale2,
                        lse_in ? lse_in : lse, lse_in ? lookm::kLog2e : 1.0f, scores);
     mark(LOOKM_K_SCORE_COLSUM);
-    return hip_ok(hipGetLastError());
+    return check.status();
+}
+
+template <typename T> static bool score_generic_attributes()
+{
+    return hipFuncSetAttribute((const void*)lookm::k_score_lse_generic<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               160 * 1024) == hipSuccess &&
+           hipFuncSetAttribute((const void*)lookm::k_score_colsum_generic<T>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                               160 * 1024) == hipSuccess;
+}
+
+int set_attributes_score_generic()
+{
+    return (score_generic_attributes<float>() && score_generic_attributes<lookm::bf16_t>()) ? LOOKM_OK : LOOKM_ERR_DEVICE;
 }
 
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)

@@ -527,6 +527,7 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
                        const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
+    const LaunchCheck check;
     const int group = H / kv_heads;
     const int nS = (L + lookm::BS - 1) / lookm::BS;
     const int C = chunk_tiles(H, L);
@@ -561,7 +562,7 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
     hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, kv_heads), dim3(256), 0, st, group, L, R0, C, part_a, part_b,
                        scores);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);
-    return hip_ok(hipGetLastError());
+    return check.status();
 }
 
 }  // namespace lookm_host

@@ -302,6 +302,7 @@ namespace lookm_host {
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int rule, int32_t* kept,
                   int32_t* evicted, int32_t* status, hipStream_t st)
 {
+    const LaunchCheck check;
     const int per_thread = (L + lookm::SEL_THREADS - 1) / lookm::SEL_THREADS;
     dim3 grid(H), block(lookm::SEL_THREADS);
     if (per_thread <= 4)
@@ -315,7 +316,7 @@ int launch_select(const float* scores, const uint8_t* mask, int H, int L, int bu
     else
         return LOOKM_ERR_UNSUPPORTED;
     mark(LOOKM_K_SELECT);
-    return hip_ok(hipGetLastError());
+    return check.status();
 }
 
 }  // namespace lookm_host

@@ -33,7 +33,8 @@ EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "loo
            "lookm_compress", "lookm_scores", "lookm_select", "lookm_nearest", "lookm_merge",
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
            "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile", "lookm_decode_workspace_bytes",
-           "lookm_decode_attention", "lookm_scores_grouped", "lookm_probe_mfma"]
+           "lookm_decode_attention", "lookm_scores_grouped", "lookm_probe_mfma", "lookm_init",
+           "lookm_compress_batch_two_streams", "lookm_workspace_offset"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -109,6 +110,12 @@ def lib() -> ctypes.CDLL:
         L.lookm_job_profile.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(ctypes.c_float), vp]
         L.lookm_compress_batch.restype = I
         L.lookm_compress_batch.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(I), vp]
+        L.lookm_compress_batch_two_streams.restype = I
+        L.lookm_compress_batch_two_streams.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(I), vp, vp]
+        L.lookm_init.restype = I
+        L.lookm_init.argtypes = []
+        L.lookm_workspace_offset.restype = sz
+        L.lookm_workspace_offset.argtypes = [I, I, I, I, I, I, I]
         L.lookm_probe_mfma.restype = I
         L.lookm_probe_mfma.argtypes = [I, I, I, I, ctypes.POINTER(ctypes.c_float), vp, sz, vp]
         _lib = L
@@ -266,14 +273,40 @@ def make_job(q, k, v, modality_mask, budget: int, recent_window: int, merge_mode
                _dev(out.status, "status"), wp, wn)
 
 
-def lookm_compress_batch(jobs) -> None:
-    """lookm_compress_batch over a list of Job structs (see make_job), on the current stream."""
+def lookm_compress_batch(jobs, aux_stream: Optional[torch.cuda.Stream] = None) -> None:
+    """lookm_compress_batch over a list of Job structs (see make_job), on the current stream; with ``aux_stream``
+    (a second stream of the caller's) lookm_compress_batch_two_streams."""
     n = len(jobs)
     arr = (Job * max(n, 1))(*jobs)
     bad = ctypes.c_int(-1)
-    rc = lib().lookm_compress_batch(arr, n, ctypes.byref(bad), _stream())
+    if aux_stream is None:
+        rc = lib().lookm_compress_batch(arr, n, ctypes.byref(bad), _stream())
+    else:
+        rc = lib().lookm_compress_batch_two_streams(arr, n, ctypes.byref(bad), _stream(), aux_stream.cuda_stream)
     if rc != OK:
         raise LookmError(rc, f"lookm_compress_batch (job {bad.value})")
+
+
+def lookm_init() -> None:
+    rc = lib().lookm_init()
+    if rc != OK:
+        raise LookmError(rc, "lookm_init")
+
+
+WS_ITEMS = {"evicted": (0, torch.int32), "assign": (1, torch.int32), "sim": (2, torch.float32)}
+
+
+def workspace_view(workspace: torch.Tensor, item: str, H: int, kv_heads: int, L: int, d: int, budget: int, dt: int):
+    """The intermediate array ``item`` ("evicted", "assign", "sim") that a finished compression call left in
+    ``workspace`` (lookm_workspace_offset): a [kv_heads, L - budget] view, no copy."""
+    code, dtype = WS_ITEMS[item]
+    off = int(lib().lookm_workspace_offset(H, kv_heads, L, d, int(budget), dt, code))
+    if off == ctypes.c_size_t(-1).value:
+        raise LookmError(ERR_INVALID_ARG, "lookm_workspace_offset")
+    base, _ = _ws_ptr(workspace)
+    start = base - workspace.data_ptr() + off
+    n = kv_heads * (L - int(budget))
+    return workspace[start:start + 4 * n].view(dtype).view(kv_heads, L - int(budget))
 
 
 def alloc_outputs(H: int, L: int, d: int, budget: int, dtype, device, want_scores: bool = False) -> Compressed:

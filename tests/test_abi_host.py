@@ -131,6 +131,23 @@ def test_batch_validates_every_job_before_any_launch():
     assert run([fake_job(d=100), fake_job()]) == lookm.ERR_UNSUPPORTED and bad.value == 0
 
 
+def test_two_stream_batch_and_workspace_offsets_validate_on_the_host():
+    L = lookm.lib()
+    bad = ctypes.c_int(-1)
+    arr = (lookm.Job * 1)(fake_job(budget=99))
+    # the second stream must differ from the first (NULL is the default stream on both sides here)
+    assert L.lookm_compress_batch_two_streams(arr, 1, ctypes.byref(bad), None, None) == lookm.ERR_INVALID_ARG
+    assert L.lookm_compress_batch_two_streams(arr, 1, ctypes.byref(bad), None, FAKE) == lookm.ERR_BUDGET_RANGE
+    assert L.lookm_compress_batch_two_streams(None, 0, None, None, FAKE) == lookm.OK
+    none = ctypes.c_size_t(-1).value
+    offs = [L.lookm_workspace_offset(32, 32, 12644, 128, 2276, lookm.BF16, item) for item in (0, 1, 2)]
+    assert all(o != none and o % 256 == 0 for o in offs) and len(set(offs)) == 3
+    assert max(offs) + 4 * 32 * (12644 - 2276) <= lookm.workspace_bytes(32, 12644, 128, 2276, lookm.BF16)
+    assert L.lookm_workspace_offset(32, 32, 12644, 128, 2276, lookm.BF16, 3) == none
+    assert L.lookm_workspace_offset(32, 5, 12644, 128, 2276, lookm.BF16, 0) == none      # 5 does not divide 32
+    assert L.lookm_workspace_offset(32, 32, 12644, 128, 20000, lookm.BF16, 0) == none
+
+
 def test_budget_from_ratios_matches_the_oracle():
     import oracle
     for L in (1, 17, 256, 4096, 12644, 32768):

@@ -96,7 +96,7 @@ def test_batch_replays_in_a_hip_graph():
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
-        lookm.lookm_compress_batch(jobs)            # warm-up on a side stream (two lanes here)
+        lookm.lookm_compress_batch(jobs)            # warm-up on a side stream
     torch.cuda.current_stream().wait_stream(side)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
@@ -111,3 +111,31 @@ def test_batch_replays_in_a_hip_graph():
         for a, b in zip(ref, outs):
             assert int(b.status.item()) == 0, rep
             assert torch.equal(a.kept_idx, b.kept_idx) and torch.equal(a.k_out, b.k_out) and torch.equal(a.v_out, b.v_out), rep
+
+
+def test_capture_of_a_shape_no_earlier_call_has_used():
+    """Kernel attributes are set for every template instance on the library's first use of a device (or by
+    lookm_init), never lazily inside a launcher: a shape whose kernels no earlier call has launched - here 20 000
+    evicted keys, the similarity-set sort with the most entries per thread - can be captured directly."""
+    dev = torch.device("cuda:0")
+    lookm.lookm_init()
+    H, L, d, B, M = 2, 21000, 128, 1000, 16
+    g = torch.Generator(device=dev).manual_seed(3)
+    q, k, v = (torch.randn((H, L, d), generator=g, device=dev).to(torch.bfloat16) for _ in range(3))
+    mask = torch.ones(L, dtype=torch.uint8, device=dev)
+    out = lookm.alloc_outputs(H, L, d, B, q.dtype, dev)
+    ws = lookm.alloc_workspace(H, L, d, B, lookm.BF16, dev)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lookm.lookm_compress(q, k, v, mask, B, M, "averaged", out=out, workspace=ws, check=False)
+    graph.replay()
+    torch.cuda.synchronize()
+    ref = lookm.lookm_compress(q, k, v, mask, B, M, "averaged")
+    for rep in range(2):
+        out.k_out.zero_(); out.kept_idx.zero_(); out.status.fill_(-99)
+        _eager_noise(dev)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(out.status.item()) == 0
+        assert torch.equal(out.kept_idx, ref.kept_idx) and torch.equal(out.k_out, ref.k_out) and torch.equal(out.v_out, ref.v_out)

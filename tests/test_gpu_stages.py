@@ -273,7 +273,7 @@ def test_nearest_matches_oracle(H, L, B, d, dtype):
     kf = k.float().numpy()
     ties = sum(parity.check_nearest(kf[h], kept[h], ev[h], a[h], s[h]) for h in range(H))
     print(f"nearest H={H} L={L} B={B} d={d}: {ties} tie-band rows")
-    assert ties <= 2
+    assert ties == 0
 
 
 def test_nearest_exact_ties_and_zero_keys():

@@ -118,3 +118,50 @@ def test_drift_guard_against_stored_oracle_outputs(tiny):
     np.testing.assert_allclose(r["scores"], np.array(g["scores"], dtype=np.float64), rtol=1e-12)
     np.testing.assert_allclose(r["k_out"].sum(-1), np.array(g["k_out_rowsum"], dtype=np.float64), rtol=1e-11, atol=1e-12)
     np.testing.assert_allclose(r["v_out"].sum(-1), np.array(g["v_out_rowsum"], dtype=np.float64), rtol=1e-11, atol=1e-12)
+
+
+# ---- grouped query heads: pins of oracle.compress_grouped ---------------------------------------------------
+
+@pytest.mark.parametrize("mode", ["averaged", "pivotal", "weighted"])
+def test_grouped_compress_with_groups_of_one_is_the_plain_path(tiny, mode):
+    # one query head per key head: the grouped composition must give what the C whole-path function gives
+    q, k, v, mask = tiny
+    w = W.TINY
+    a = oracle.compress_grouped(q, k, v, mask, w.budget(), w.M, mode)
+    b = oracle.compress(q, k, v, mask, w.budget(), w.M, mode)
+    for name in ("scores", "kept", "evicted", "assign", "sim", "k_out", "v_out"):
+        np.testing.assert_array_equal(a[name], b[name], err_msg=name)
+
+
+def test_grouped_compress_pinned_by_twin_and_by_silent_query_heads():
+    """Two pins that do not go through the grouped code itself.  (i) A group made of two identical query heads
+    scores every key exactly twice what one of them does (x + x is exact), so selection, matching and merging are
+    those of the single head.  (ii) A group of one ordinary and one all-zero query head: the zero head attends
+    uniformly, so its column sums are the harmonic tail H_L - H_j, a closed form added to the single head's scores;
+    the kept sets are then the single-head selection applied to that sum."""
+    rng = np.random.default_rng(7)
+    L, d, B, M = 96, 16, 40, 8
+    mask = (rng.random(L) < 0.7).astype(np.uint8)
+    B = max(B, oracle.protected_count(mask, M) + 5)
+    q = rng.standard_normal((1, L, d)).astype(np.float32)
+    k = rng.standard_normal((1, L, d)).astype(np.float32)
+    v = rng.standard_normal((1, L, d)).astype(np.float32)
+    single = oracle.compress(q, k, v, mask, B, M, "weighted")
+    twin = oracle.compress_grouped(np.concatenate([q, q]), k, v, mask, B, M, "weighted")
+    np.testing.assert_array_equal(twin["scores"], 2.0 * single["scores"])
+    for name in ("kept", "evicted", "assign", "sim", "k_out", "v_out"):
+        np.testing.assert_array_equal(twin[name], single[name], err_msg=name)
+    silent = oracle.compress_grouped(np.concatenate([q, np.zeros_like(q)]), k, v, mask, B, M, "averaged")
+    harmonic_tail = np.cumsum((1.0 / np.arange(1, L + 1))[::-1])[::-1]
+    np.testing.assert_allclose(silent["scores"][0], single["scores"][0] + harmonic_tail, rtol=1e-12)
+    kept, ev = oracle.select(single["scores"][0] + harmonic_tail, mask, B, M)
+    # selection is discontinuous: compare only if the summed scores are not within rounding of a tie at the threshold
+    comp = np.flatnonzero((mask == 1) & (np.arange(L) < L - M))
+    s = np.sort((single["scores"][0] + harmonic_tail)[comp])[::-1]
+    n_img = B - oracle.protected_count(mask, M)
+    assert s[n_img - 1] - s[n_img] > 1e-9
+    assert silent["kept"][0].tolist() == kept.tolist() and silent["evicted"][0].tolist() == ev.tolist()
+    a, sm = oracle.nearest(k[0], kept, ev)
+    np.testing.assert_array_equal(silent["assign"][0], a)
+    np.testing.assert_array_equal(silent["k_out"][0], oracle.merge(k[0], kept, ev, a, sm, "averaged"))
+    np.testing.assert_array_equal(silent["v_out"][0], oracle.merge(v[0], kept, ev, a, sm, "averaged"))
