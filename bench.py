@@ -171,6 +171,9 @@ def main() -> int:
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
     ap.add_argument("--score-window", type=int, default=0,
                     help="variant: scores from the last W query rows only (lookm_scores_window), via a lookm_job")
+    ap.add_argument("--split-heads", type=int, default=0,
+                    help="issue the layer as this many jobs over equal groups of heads through ONE "
+                         "lookm_compress_batch_two_streams call (0: one lookm_compress call on one stream)")
     ap.add_argument("--probe-mfma", action="store_true",
                     help="only measure the sustained rate of the bf16 MFMA instruction from registers (constant and "
                          "random operands, 1-3 waves per SIMD) and exit")
@@ -238,8 +241,30 @@ def main() -> int:
     variant = args.reuse_lse or args.score_window > 0
     job = lookm.make_job(qg, kg, vg, mg, B, M, mode, out, ws, row_lse=row_lse, score_window=args.score_window)
 
+    split_jobs, aux = None, None
+    if args.split_heads > 1:
+        # the same layer as independent jobs over groups of heads (own workspace, own slice of the outputs), handed to
+        # the library in one call with a second stream: the short kernels of one group run under the long ones of another
+        n = args.split_heads
+        assert w.H % n == 0
+        g = w.H // n
+        aux = torch.cuda.Stream()
+        dtc = lookm.BF16 if w.dtype == "bf16" else lookm.F32
+        split_jobs, split_keep = [], []
+        for i in range(n):
+            sl = slice(i * g, (i + 1) * g)
+            o = lookm.Compressed(out.k_out[sl], out.v_out[sl], out.kept_idx[sl], None,
+                                 torch.zeros(1, dtype=torch.int32, device=dev))
+            wsi = lookm.alloc_workspace(g, w.L, w.d, B, dtc, dev)
+            split_keep.append((o, wsi))
+            split_jobs.append(lookm.make_job(qg[sl], kg[sl], vg[sl], mg, B, M, mode, o, wsi,
+                                             row_lse=None if row_lse is None else row_lse[sl],
+                                             score_window=args.score_window))
+
     def step():
-        if variant:
+        if split_jobs is not None:
+            lookm.lookm_compress_batch(split_jobs, aux_stream=aux)
+        elif variant:
             lookm.lookm_compress_batch([job])
         else:
             lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
@@ -253,7 +278,7 @@ def main() -> int:
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    status = int(out.status.item())
+    status = int(out.status.item()) if split_jobs is None else min(int(o.status.item()) for o, _ in split_keep)
     if status != 0:
         print(f"bench.py: device status {status}", file=sys.stderr)
         return 1
@@ -343,7 +368,8 @@ def main() -> int:
                                f"{len(w.spans)} text spans, L={w.L}, budget B={B} (k_img={w.k_img()}), "
                                f"recent_window={M}, merge={mode}",
                    "H": w.H, "L": w.L, "d": w.d, "budget": B, "recent_window": M, "merge_mode": mode,
-                   "row_lse_supplied": bool(args.reuse_lse), "score_window": args.score_window},
+                   "row_lse_supplied": bool(args.reuse_lse), "score_window": args.score_window,
+                   "split_heads": args.split_heads},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
         "kernels": kernels,

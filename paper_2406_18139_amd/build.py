@@ -27,7 +27,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-tar
 
 def _compile(src: str) -> Path:
     obj = OBJ / (src + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", str(CSRC / src), "-o", str(obj)]
+    cmd = [HIPCC, *FLAGS, *os.environ.get("LOOKM_EXTRA_FLAGS", "").split(), "-c", str(CSRC / src), "-o", str(obj)]
     p = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in p.stderr.splitlines() if "not a recognized feature" not in l)
     if p.returncode != 0:

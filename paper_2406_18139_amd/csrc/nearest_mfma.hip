@@ -17,12 +17,16 @@
 //
 // Exact decisions.  The matrix-core value of y differs from the true one by well under one unit (fp32
 // accumulation of exact products, one fp32 inverse norm, one product: a few ulp), so the true maximum can only
-// be a key whose truncated value lies within NEAR_UNITS units of the best one.  k_nearest_fold therefore takes
-// the matrix-core choice only where the runner-up is farther away than that; every other evicted key (a few per
-// ten thousand) is decided again by an exact pass: all conserved keys within a wide band of the best are
-// evaluated in binary64 with a fixed arithmetic contract - sequential sums over k = 0..d-1 of products that are
-// exact in binary64, binary64 square roots, one product, one division, first maximum in slot order - which is a
-// definition, not an approximation, so any implementation of the same contract takes the same decision.
+// be a key whose truncated value lies within NEAR_UNITS units of the best one.  Besides the best key, a lane
+// therefore keeps (i) the largest runner-up INSIDE a 32x32 block it has seen and (ii) a bit mask of the blocks
+// whose best value came within NEAR_UNITS units of its running best (cleared whenever the best jumps by more
+// than that, so that at the end it marks exactly the blocks that can still hold a contender).  k_nearest_fold
+// takes the matrix-core choice where the winner's block is the only marked one and its runner-up inside the
+// block is farther away; every other evicted key (one in six hundred at the headline shape) is decided again
+// exactly: the slots of the marked blocks are evaluated in binary64 with a fixed arithmetic contract -
+// sequential sums over k = 0..d-1 of products that are exact in binary64, binary64 square roots, one product,
+// one division, first maximum in slot order - which is a definition, not an approximation, so any
+// implementation of the same contract takes the same decision.
 //
 // The conserved axis is cut into chunks (one workgroup per (evicted strip, chunk)) chosen so that the
 // number of workgroups fills the resident slots evenly; enumeration is chunk-major and XCD-affine as in
@@ -42,13 +46,19 @@ static_assert(NBX == 64, "the norms of a tile are staged by wave 0, one row per 
 
 constexpr int NEAR_UNITS = 2;   // a runner-up within this many units of the best truncated value: decided exactly
 
-// partial result of one (evicted strip, chunk): truncated value (float bits of y >> 4) and slot of the best
-// conserved key, truncated value of the runner-up
+// partial result of one (evicted strip, chunk), the lane pair that shares an evicted key already merged:
+//   key   (truncated value of the best conserved key) << 4 | how many units the best runner-up inside a block of the
+//         winning lane lies below it (15 = fifteen or more)
+//   slot  the best key's slot
+//   marks bits 0-15 and 16-31: per lane of the pair (first: slots 0-3 of every eight, second: slots 4-7), bit b set
+//         if the blocks b, b + 16, ... of the chunk can hold a key within NEAR_UNITS units of the chunk's best
+//         value; zero for a lane whose own best value is farther away than that
 struct NearestPartial {
     int32_t key;
     int32_t slot;
-    int32_t second;
+    uint32_t marks;
 };
+constexpr int NEAR_MASK_BITS = 16;
 
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
 __device__ __forceinline__ int imed3(int a, int b, int c) { return max(min(a, b), min(max(a, b), c)); }
@@ -168,9 +178,11 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
 
     // per stationary row of this lane; the initial state is below every key and decodes to slot 0
     constexpr int KEY_MIN = (int)0x80000000;
+    constexpr int NEAR_KEY = (NEAR_UNITS << 4) + 15;   // NEAR_UNITS units, in keys (whose low 4 bits are tags)
     int bkey[2] = {KEY_MIN | 15, KEY_MIN | 15};   // best key (low 4 bits: 15 - entry number)
-    int bsec[2] = {KEY_MIN, KEY_MIN};             // runner-up key
+    int bsec[2] = {KEY_MIN, KEY_MIN};             // largest runner-up inside one block
     int bxb[2] = {0, 0};                          // slot of entry 0 of the block the best key came from
+    uint32_t bnear[2] = {0u, 0u};                 // blocks (mod 16) that can still hold a contender
 
     LOOKM_LOAD_INDEX(x_begin);           // in flight together with the evicted positions
 
@@ -219,6 +231,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], acc[1], 0, 0, 0);
             }
             const int xb = x0 + rb * 32 + 4 * half;   // slot of entry r: xb + 8*(r/4) + r%4
+            const uint32_t blk_bit = 1u << ((2 * it + rb) & (NEAR_MASK_BITS - 1));
             const float* rp = &cur_r[rb * 32 + 4 * half];
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
@@ -238,7 +251,12 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 int bm, bs2;
                 top2_of_16(u, bm, bs2);
                 const bool better = (bm >> 4) > (bkey[cb] >> 4);   // strict: an equal value in a later block loses
-                bsec[cb] = imax3(min(bkey[cb], bm), bsec[cb], bs2);
+                // a jump by more than the band leaves every earlier block out of reach; a block within the band of
+                // the running best (from either side) stays a candidate
+                const int ahead = __builtin_elementwise_sub_sat(bm, bkey[cb]);   // saturating: the first block's lead is huge
+                bnear[cb] = (ahead > NEAR_KEY) ? 0u : bnear[cb];
+                bnear[cb] |= (ahead >= -NEAR_KEY) ? blk_bit : 0u;
+                bsec[cb] = max(bsec[cb], bs2);
                 bkey[cb] = better ? bm : bkey[cb];
                 bxb[cb] = better ? xb : bxb[cb];
             }
@@ -262,15 +280,19 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         const int r = 15 - (bkey[cb] & 15);
         int slot = bxb[cb] + 8 * (r >> 2) + (r & 3);
         int hi = bkey[cb] >> 4, sec = bsec[cb] >> 4;
+        uint32_t mine = bnear[cb];
         const int ohi = __shfl_xor(hi, 32), oslot = __shfl_xor(slot, 32), osec = __shfl_xor(sec, 32);
+        uint32_t theirs = (uint32_t)__shfl_xor((int)mine, 32);
         const bool other = ohi > hi || (ohi == hi && oslot < slot);
-        sec = imax3(other ? hi : ohi, sec, osec);       // the loser of the pair is a runner-up candidate
-        if (other) { hi = ohi; slot = oslot; }
+        // the losing lane's blocks only matter if its best value is within the band of the winner's
+        if (other) mine = (hi >= ohi - NEAR_UNITS) ? mine : 0u;
+        else theirs = (ohi >= hi - NEAR_UNITS) ? theirs : 0u;
+        if (other) { hi = ohi; slot = oslot; sec = osec; }
         if (half == 0) {
             NearestPartial p;
-            p.key = hi;
+            p.key = (int)(((uint32_t)hi << 4) | (uint32_t)min(hi - sec, 15));   // sec <= hi
             p.slot = slot;
-            p.second = sec;
+            p.marks = mine | (theirs << 16);
             out[wave * 64 + cb * 32 + n] = p;
         }
     }
@@ -278,21 +300,47 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
 
 // cosine of two keys under the exact contract: sequential binary64 sums over k = 0..127 (every product of two
 // bf16 values is exact in binary64, so a fused multiply-add gives the same bits as multiply-then-add), binary64
-// square roots (correctly rounded), one product, one division; 0 when either norm vanishes.
+// square roots (correctly rounded), one product, one division; 0 when either norm vanishes.  Both rows come from
+// global memory an eighth at a time, the next eighth in flight while one is summed (a loop, not unrolled
+// further: this runs on a handful of threads per call).
 __device__ __forceinline__ double cosine_exact(const bf16_t* __restrict__ a, const bf16_t* __restrict__ b)
 {
     double na = 0.0, nb = 0.0, ab = 0.0;
-#pragma unroll 1
-    for (int c0 = 0; c0 < ND; c0 += 8) {
-        float x[8], y[8];
-        load8(a + c0, x);
-        load8(b + c0, y);
+    uint4 an[2], bn[2];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const double xa = (double)x[i], yb = (double)y[i];
-            na = fma(xa, xa, na);
-            nb = fma(yb, yb, nb);
-            ab = fma(xa, yb, ab);
+    for (int j = 0; j < 2; ++j) {
+        an[j] = *reinterpret_cast<const uint4*>(a + 8 * j);
+        bn[j] = *reinterpret_cast<const uint4*>(b + 8 * j);
+    }
+    // a row is two cache lines: the second ones are asked for now, so that only one memory latency is paid per row
+    uint4 a_mid = *reinterpret_cast<const uint4*>(a + 64), b_mid = *reinterpret_cast<const uint4*>(b + 64);
+#pragma unroll 1
+    for (int q = 0; q < 8; ++q) {
+        uint4 ac[2], bc[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) { ac[j] = an[j]; bc[j] = bn[j]; }
+        if (q < 7) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                an[j] = *reinterpret_cast<const uint4*>(a + 16 * (q + 1) + 8 * j);
+                bn[j] = *reinterpret_cast<const uint4*>(b + 16 * (q + 1) + 8 * j);
+            }
+            if (q == 3) { an[0] = a_mid; bn[0] = b_mid; }      // element 64: already here
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint32_t aw[4] = {ac[j].x, ac[j].y, ac[j].z, ac[j].w}, bw[4] = {bc[j].x, bc[j].y, bc[j].z, bc[j].w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const double xa = (double)__uint_as_float((i & 1) ? (aw[i >> 1] & 0xffff0000u) : (aw[i >> 1] << 16));
+                const double yb = (double)__uint_as_float((i & 1) ? (bw[i >> 1] & 0xffff0000u) : (bw[i >> 1] << 16));
+                na = fma(xa, xa, na);
+                nb = fma(yb, yb, nb);
+                ab = fma(xa, yb, ab);
+            }
+            // the three sums advance together (left alone, the compiler finishes one sum before it starts the next
+            // and keeps every widened value alive in between, which spills)
+            asm volatile("" : "+v"(na), "+v"(nb), "+v"(ab));
         }
     }
     if (na == 0.0 || nb == 0.0) return 0.0;
@@ -300,117 +348,179 @@ __device__ __forceinline__ double cosine_exact(const bf16_t* __restrict__ a, con
 }
 
 constexpr int NF_THREADS = 256;
-constexpr int NF_CAND = 1024;     // capacity of the candidate list of the exact pass
+constexpr int NF_ITEMS = 768;     // (evicted key, candidate slot) pairs evaluated exactly per round of a workgroup
+constexpr int NF_LDS_CHUNKS = 4;  // chunks whose block masks the fold keeps in LDS (further chunks are read again)
 
-// Folds the chunks of every evicted key (value descending, slot ascending) and carries the runner-up along:
-// one thread per evicted key.  Where the runner-up is more than NEAR_UNITS units below the best value the
-// matrix-core choice stands: assign[h, e] = its slot, sim[h, e] = the cosine decoded from the centre of the
-// key's truncation interval (|error| < 1.2e-6).  Every other key of the workgroup is decided by the exact pass:
-// 16 lanes per conserved key recompute y in fp32 (coalesced row reads) and list the slots within a wide band
-// (3e-5 relative) below the best value - or all slots when the best value is not positive - and the listed
-// slots are evaluated with cosine_exact; the first maximum in slot order wins and its cosine is returned.
-__global__ void __launch_bounds__(NF_THREADS)
+// Folds the chunks of every evicted key (value descending, slot ascending): one thread per evicted key.  Where
+// the winner's block is the only marked block of all chunks whose best value is within NEAR_UNITS units of the
+// overall best, and the winner's lane saw no runner-up inside a block within that distance, the matrix-core choice
+// stands: assign[h, e] = its slot, sim[h, e] = the cosine decoded from the centre of the key's truncation interval
+// (|error| < 1.2e-6).  The other keys of the workgroup are decided exactly, together: their threads list the slots
+// of the marked blocks as (key, slot) items in LDS, every thread of the workgroup evaluates items with
+// cosine_exact, and each key's thread then takes the first maximum in slot order and returns its cosine.  A key
+// whose best value is not positive (integer order of the bits is not float order there) takes every slot.
+// (few registers and little LDS on purpose: all workgroups of the headline shape are resident at once, so the
+// kernel takes as long as its slowest workgroup, not twice that)
+__global__ void __launch_bounds__(NF_THREADS, 6)
 k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
-               const int32_t* __restrict__ evicted, int L, int B, int Le, int n_strips, int n_chunks,
+               const int32_t* __restrict__ evicted, int L, int B, int Le, int n_strips, int n_chunks, int CT,
                const NearestPartial* __restrict__ part, int32_t* __restrict__ assign, float* __restrict__ sim)
 {
-    __shared__ int todo[NF_THREADS];          // evicted-list indices that need the exact pass
-    __shared__ float todo_y[NF_THREADS];      // their best matrix-core value (<= 0: no band, every slot is listed)
-    __shared__ int cand[NF_CAND];
-    __shared__ double red_s[NF_THREADS];
-    __shared__ int red_r[NF_THREADS];
-    __shared__ int n_todo, n_cand;
+    __shared__ int item_pos_e[NF_ITEMS];      // position of the item's evicted key, or -1 for an empty entry
+    __shared__ int item_pos_c[NF_ITEMS];      // position of the item's conserved key
+    __shared__ int item_slot[NF_ITEMS];
+    __shared__ double item_s[NF_ITEMS];
+    __shared__ uint32_t near_m[NF_LDS_CHUNKS][NF_THREADS];   // marked blocks per key and chunk (both lanes' masks); 0: chunk out of reach
+    __shared__ int n_items;
     const int h = blockIdx.y, tid = threadIdx.x;
-    const int ev = blockIdx.x * NF_THREADS + tid;
     k += (size_t)h * L * ND;
     rnorm += (size_t)h * L;
     kept += (size_t)h * B;
     evicted += (size_t)h * Le;
     assign += (size_t)h * Le;
     sim += (size_t)h * Le;
-    if (tid == 0) n_todo = 0;
-    __syncthreads();
+    const int ev = blockIdx.x * NF_THREADS + tid;
+
+    bool pending = false;                     // this thread's key still needs the exact decision
+    int pos_e = 0, bk = 0;
+    const NearestPartial* mine = part;        // this key's partial of chunk 0; chunk c is n_strips * NBS entries further
     if (ev < Le) {
-        const int strip = ev / NBS, r = ev % NBS;
-        int bk = (int)0x80000000, bs = 0x7fffffff, sec = (int)0x80000000;
-        for (int c = 0; c < n_chunks; ++c) {
-            const NearestPartial p = part[(((size_t)h * n_chunks + c) * n_strips + strip) * NBS + r];
-            const bool better = p.key > bk || (p.key == bk && p.slot < bs);
-            sec = imax3(better ? bk : p.key, sec, p.second);
-            if (better) { bk = p.key; bs = p.slot; }
+        pos_e = evicted[ev];
+        mine = part + ((size_t)h * n_chunks * n_strips + ev / NBS) * NBS + ev % NBS;
+        int key[8], bs = 0x7fffffff, bd = 15, marks[8];
+        bk = (int)0x80000000;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            key[c] = (int)0x80000000;
+            marks[c] = 0;
+            if (c < n_chunks) {
+                const NearestPartial p = mine[(size_t)c * n_strips * NBS];
+                key[c] = p.key >> 4;
+                marks[c] = __popc(p.marks);
+                if (c < NF_LDS_CHUNKS) near_m[c][tid] = p.marks;
+                if (key[c] > bk || (key[c] == bk && p.slot < bs)) { bk = key[c]; bs = p.slot; bd = p.key & 15; }
+            }
         }
-        const float y = __uint_as_float(((uint32_t)bk << 4) | 8u);     // (k_e.k_c) * rnorm_c, centre of the interval
-        // bk <= 0: the best value is zero or negative (integer order is not float order there)
-        if (bk <= 0 || sec >= bk - NEAR_UNITS) {
-            const int i = atomicAdd(&n_todo, 1);     // the order of this list decides no result
-            todo[i] = ev;
-            todo_y[i] = (bk > 0) ? y : 0.f;
-        } else {
+        int marked = 0;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const bool reach = key[c] >= bk - NEAR_UNITS;          // chunks within reach only
+            marked += reach ? marks[c] : 0;
+            if (c < NF_LDS_CHUNKS && c < n_chunks && !reach) near_m[c][tid] = 0u;
+        }
+        // bk <= 0: the best value is zero or negative; every slot is a candidate then
+        pending = bk <= 0 || bd <= NEAR_UNITS || marked > 1;
+        if (!pending) {
+            const float y = __uint_as_float(((uint32_t)bk << 4) | 8u);     // (k_e.k_c) * rnorm_c, centre of the interval
             assign[ev] = min(max(bs, 0), B - 1);
-            sim[ev] = y * rnorm[evicted[ev]];
+            sim[ev] = y * rnorm[pos_e];
         }
     }
-    __syncthreads();
-    const int nt = n_todo;
-    const int grp = tid >> 4, c0 = (tid & 15) * 8;
-    for (int t = 0; t < nt; ++t) {
-        const int e = todo[t];
-        const float ybest = todo_y[t];
-        const bf16_t* ke = k + (size_t)evicted[e] * ND;
-        if (tid == 0) n_cand = 0;
-        __syncthreads();
-        if (ybest > 0.f) {
-            float xe[8];
-            load8(ke + c0, xe);
-            const float bound = ybest * (1.0f - 3.0e-5f);
-            for (int r0 = 0; r0 < B; r0 += NF_THREADS / 16) {
-                const int r = min(r0 + grp, B - 1);
-                const int pos = kept[r];
-                float xc[8];
-                load8(k + (size_t)pos * ND + c0, xc);
-                float dot = 0.f;
+    if (!__syncthreads_or(pending)) return;
+
+    // The marked blocks of chunk c for this thread's key (zero when the chunk is out of reach).
+    auto chunk_marks = [&](int c, uint32_t (&m)[2]) {
+        uint32_t both;
+        if (c < NF_LDS_CHUNKS) both = near_m[c][tid];
+        else {                                                         // more chunks than LDS holds: read again
+            const NearestPartial p = mine[(size_t)c * n_strips * NBS];
+            both = ((p.key >> 4) >= bk - NEAR_UNITS) ? p.marks : 0u;
+        }
+        m[0] = both & 0xffffu;
+        m[1] = both >> 16;
+    };
+    // Walks through the candidate slots of this thread's key - the 16 slots of every marked block of every chunk
+    // within reach, or every slot when the best value is not positive; slots past the end of the conserved list
+    // are reported as -1 (so that a block always yields 16 entries).  Bit b of a mask stands for the blocks b,
+    // b + 16, ... of the chunk.
+    auto for_each_candidate = [&](auto&& visit) {
+        if (bk <= 0) {
+            for (int s = 0; s < B; ++s) visit(s);
+            return;
+        }
+        for (int c = 0; c < n_chunks; ++c) {
+            uint32_t m[2];
+            chunk_marks(c, m);
+            const int lo = c * CT, hi = min(B, lo + CT);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) dot = fmaf(xe[i], xc[i], dot);
-                dot += __shfl_xor(dot, 1);
-                dot += __shfl_xor(dot, 2);
-                dot += __shfl_xor(dot, 4);
-                dot += __shfl_xor(dot, 8);
-                if ((tid & 15) == 0 && r0 + grp < B && dot * rnorm[pos] >= bound) {
-                    const int i = atomicAdd(&n_cand, 1);
-                    if (i < NF_CAND) cand[i] = r;
+            for (int half = 0; half < 2; ++half) {
+                for (uint32_t rest = m[half]; rest != 0u; rest &= rest - 1u) {
+                    for (int b = __ffs((int)rest) - 1; lo + 32 * b < hi; b += NEAR_MASK_BITS) {
+                        for (int g = 0; g < 16; ++g) {
+                            const int s = lo + 32 * b + 4 * half + 8 * (g >> 2) + (g & 3);
+                            visit(s < hi ? s : -1);
+                        }
+                    }
                 }
             }
         }
-        __syncthreads();
-        const int nc = n_cand;
-        const bool all = !(ybest > 0.f) || nc > NF_CAND || nc == 0;      // no band, or more candidates than the list holds
-        const int count = all ? B : nc;
-        double best_s = 0.0;
-        int best_r = 0x7fffffff;
-        for (int i = tid; i < count; i += NF_THREADS) {
-            const int r = all ? i : cand[i];
-            const double s = cosine_exact(ke, k + (size_t)kept[r] * ND);
-            if (best_r == 0x7fffffff || s > best_s || (s == best_s && r < best_r)) { best_s = s; best_r = r; }
-        }
-        red_s[tid] = best_s;
-        red_r[tid] = best_r;
-        __syncthreads();
-        for (int off = NF_THREADS / 2; off > 0; off >>= 1) {
-            if (tid < off) {
-                const double s2 = red_s[tid + off];
-                const int r2 = red_r[tid + off];
-                if (r2 != 0x7fffffff && (red_r[tid] == 0x7fffffff || s2 > red_s[tid] || (s2 == red_s[tid] && r2 < red_r[tid]))) {
-                    red_s[tid] = s2;
-                    red_r[tid] = r2;
-                }
+    };
+    int cnt = 0;
+    if (pending) {
+        if (bk <= 0) cnt = B;
+        else
+            for (int c = 0; c < n_chunks; ++c) {
+                uint32_t m[2];
+                chunk_marks(c, m);
+                const int nb = (min(B, (c + 1) * CT) - c * CT + 31) / 32;      // blocks of this chunk
+#pragma unroll
+                for (int half = 0; half < 2; ++half)
+                    for (uint32_t rest = m[half]; rest != 0u; rest &= rest - 1u) {
+                        const int b = __ffs((int)rest) - 1;
+                        cnt += (b < nb) ? 16 * ((nb - b + NEAR_MASK_BITS - 1) / NEAR_MASK_BITS) : 0;
+                    }
             }
-            __syncthreads();
+    }
+    while (true) {
+        for (int i = tid; i < NF_ITEMS; i += NF_THREADS) item_pos_e[i] = -1;
+        if (tid == 0) n_items = 0;
+        __syncthreads();
+        // keys whose items fit into this round's list write them (whoever reserves first always fits if its count
+        // is at most the capacity; the order of the reservations decides no result)
+        int base = -1;
+        if (pending && cnt <= NF_ITEMS) {
+            base = atomicAdd(&n_items, cnt);
+            if (base + cnt > NF_ITEMS) base = -1;
         }
-        if (tid == 0) {
-            assign[e] = (red_r[0] == 0x7fffffff) ? 0 : red_r[0];
-            sim[e] = (float)red_s[0];
+        if (base >= 0) {
+            int at = base;
+            for_each_candidate([&](int s) {
+                item_pos_e[at] = (s >= 0) ? pos_e : -1;
+                item_pos_c[at] = kept[max(s, 0)];            // independent loads: one memory latency for all of them
+                item_slot[at] = s;
+                ++at;
+            });
         }
         __syncthreads();
+        const int n = min(n_items, NF_ITEMS);
+        for (int i = tid; i < n; i += NF_THREADS) {
+            const int pe = item_pos_e[i];
+            if (pe >= 0) item_s[i] = cosine_exact(k + (size_t)pe * ND, k + (size_t)item_pos_c[i] * ND);
+        }
+        __syncthreads();
+        if (base >= 0 || (pending && cnt > NF_ITEMS)) {
+            double best_s = 0.0;
+            int best_r = 0x7fffffff;
+            if (base >= 0) {
+                for (int i = base; i < base + cnt; ++i) {
+                    if (item_pos_e[i] < 0) continue;
+                    const double s = item_s[i];
+                    const int r = item_slot[i];
+                    if (best_r == 0x7fffffff || s > best_s || (s == best_s && r < best_r)) { best_s = s; best_r = r; }
+                }
+            } else {
+                // more candidates than a round holds (many keys of equal direction): this thread walks through them alone
+                for_each_candidate([&](int s) {
+                    if (s < 0) return;
+                    const double c = cosine_exact(k + (size_t)pos_e * ND, k + (size_t)kept[s] * ND);
+                    if (best_r == 0x7fffffff || c > best_s || (c == best_s && s < best_r)) { best_s = c; best_r = s; }
+                });
+            }
+            assign[ev] = (best_r == 0x7fffffff) ? 0 : best_r;
+            sim[ev] = (float)best_s;
+            pending = false;
+        }
+        if (!__syncthreads_or(pending)) break;
     }
 }
 
@@ -455,12 +565,13 @@ int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evict
     if (H >= 8) grid = 8u * (unsigned)((H + 7) / 8) * (unsigned)U;
     else { const int xph = 8 / H; grid = 8u * (unsigned)((U + xph - 1) / xph); }
     lookm::NearestPartial* part = (lookm::NearestPartial*)scratch;
-    hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3(grid), dim3(256), 0, st, (const lookm::bf16_t*)k, rnorm, kept,
-                       evicted, H, L, B, Le, strips, n_chunks, CT, part);
+    const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
+    hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3(grid), dim3(256), 0, st, kk, rnorm, kept, evicted, H, L, B, Le, strips,
+                       n_chunks, CT, part);
     mark(LOOKM_K_NEAREST);
     hipLaunchKernelGGL(lookm::k_nearest_fold, dim3((Le + lookm::NF_THREADS - 1) / lookm::NF_THREADS, H),
-                       dim3(lookm::NF_THREADS), 0, st, (const lookm::bf16_t*)k, rnorm, kept, evicted, L, B, Le, strips,
-                       n_chunks, part, assign, sim);
+                       dim3(lookm::NF_THREADS), 0, st, kk, rnorm, kept, evicted, L, B, Le, strips, n_chunks, CT, part,
+                       assign, sim);
     mark(LOOKM_K_NEAREST_FOLD);
     return check.status();
 }
