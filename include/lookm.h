@@ -303,6 +303,22 @@ size_t lookm_decode_workspace_bytes(int H, int d);
 int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cache, int H, int rows, int S, int d,
                            lookm_dtype dt, void* out, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/*
+ * For callers that cannot allocate device memory or hand over a workspace - code running under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: lookm_decode_attention with its partial results kept in a
+ * buffer of LOOKM_DECODE_NOALLOC_SCRATCH_BYTES that the library holds in static device memory (one copy per GPU the
+ * library runs on, until the process ends).  Same kernels, same results bit for bit.  The call allocates and frees
+ * nothing (its first call on a device, or lookm_init, looks up the buffer's device address).
+ *   Sizes whose partial results (H x pieces x (d + 2) floats, pieces <= 256 growing with S) exceed the buffer are
+ *   refused with LOOKM_ERR_WORKSPACE before anything is launched; 32 heads x d 128 fit at any S.
+ *   All calls on one GPU share the buffer: calls that may overlap in time (different streams, different host
+ *   threads) race on it - keep them on one stream or order them yourself.
+ * Other arguments and errors as for lookm_decode_attention.
+ */
+#define LOOKM_DECODE_NOALLOC_SCRATCH_BYTES (8u << 20)
+int lookm_decode_attention_noalloc(const void* q, const void* k_cache, const void* v_cache, int H, int rows, int S,
+                                   int d, lookm_dtype dt, void* out, void* hip_stream);
+
 /* ---- measurement aid ------------------------------------------------------------------------------- */
 
 /* Intermediate results that lookm_compress (or a job) leaves in its workspace, for callers that want to inspect

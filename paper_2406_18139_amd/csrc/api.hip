@@ -217,7 +217,7 @@ int ensure_device_ready()
     std::lock_guard<std::mutex> lock(g_ready_mutex);
     if (g_ready[dev]) return LOOKM_OK;
     if (set_attributes_score_generic() != LOOKM_OK || set_attributes_nearest_generic() != LOOKM_OK ||
-        set_attributes_merge() != LOOKM_OK)
+        set_attributes_merge() != LOOKM_OK || decode_static_scratch_setup() != LOOKM_OK)
         return LOOKM_ERR_DEVICE;
     g_ready[dev] = true;
     return LOOKM_OK;
@@ -541,6 +541,24 @@ int lookm_decode_attention(const void* q, const void* k_cache, const void* v_cac
     if (rdy != LOOKM_OK) return rdy;
     return lookm_host::launch_decode(q, k_cache, v_cache, H, rows, S, d, dt, out, static_cast<float*>(workspace),
                                      (hipStream_t)hip_stream);
+}
+
+int lookm_decode_attention_noalloc(const void* q, const void* k_cache, const void* v_cache, int H, int rows, int S, int d,
+                                   lookm_dtype dt, void* out, void* hip_stream)
+{
+    if (!q || !k_cache || !v_cache || !out) return LOOKM_ERR_INVALID_ARG;
+    if (H <= 0 || rows <= 0 || S <= 0 || S > rows || d <= 0) return LOOKM_ERR_INVALID_ARG;
+    if (dt != LOOKM_F32 && dt != LOOKM_BF16) return LOOKM_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 256) return LOOKM_ERR_UNSUPPORTED;
+    if ((double)H * (double)rows * (double)d >= 1099511627776.0) return LOOKM_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache) || !aligned16(out)) return LOOKM_ERR_INVALID_ARG;
+    // sizes whose partial results do not fit the static array are refused, before anything is launched
+    if (lookm_host::decode_partial_bytes(H, S, d) > (size_t)LOOKM_DECODE_NOALLOC_SCRATCH_BYTES) return LOOKM_ERR_WORKSPACE;
+    const int rdy = lookm_host::ensure_device_ready();      // first call on a device: resolves the array's address
+    if (rdy != LOOKM_OK) return rdy;
+    float* part = lookm_host::decode_static_scratch();
+    if (part == nullptr) return LOOKM_ERR_DEVICE;
+    return lookm_host::launch_decode(q, k_cache, v_cache, H, rows, S, d, dt, out, part, (hipStream_t)hip_stream);
 }
 
 int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, void* hip_stream)

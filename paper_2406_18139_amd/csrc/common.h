@@ -97,6 +97,9 @@ int launch_merge(const void* k, const void* v, const int32_t* kept, const int32_
 int launch_decode(const void* q, const void* k, const void* v, int H, int rows, int S, int d, lookm_dtype dt, void* out,
                   float* part, hipStream_t st);
 size_t decode_scratch_bytes(int H, int d);
+size_t decode_partial_bytes(int H, int S, int d);
+int decode_static_scratch_setup();     // once per device: resolves the device address of the static scratch array
+float* decode_static_scratch();        // that address for the current device (null before the set-up)
 
 inline int hip_ok(hipError_t e) { return e == hipSuccess ? LOOKM_OK : LOOKM_ERR_DEVICE; }
 

@@ -11,6 +11,8 @@
 // result is bitwise repeatable.
 #include "common.h"
 
+#include <mutex>
+
 namespace lookm {
 
 constexpr int DC_THREADS = 256;
@@ -177,6 +179,14 @@ static int decode_pieces(int H, int S, int G)
 
 size_t decode_scratch_bytes(int H, int d) { return (size_t)H * lookm::DC_MAX_SPLIT * (d + 2) * sizeof(float); }
 
+// bytes of partial results one call really writes and reads (at most decode_scratch_bytes)
+size_t decode_partial_bytes(int H, int S, int d)
+{
+    int G = 1;
+    while (G * 8 < d) G <<= 1;
+    return (size_t)H * decode_pieces(H, S, G) * (d + 2) * sizeof(float);
+}
+
 template <typename T>
 static int launch_decode_t(const T* q, const T* k, const T* v, int H, int rows, int S, int d, T* out, float* part,
                            hipStream_t st)
@@ -203,6 +213,39 @@ int launch_decode(const void* q, const void* k, const void* v, int H, int rows, 
         return launch_decode_t((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, (const lookm::bf16_t*)v, H, rows, S, d,
                                (lookm::bf16_t*)out, part, st);
     return launch_decode_t((const float*)q, (const float*)k, (const float*)v, H, rows, S, d, (float*)out, part, st);
+}
+
+// ---- scratch for callers that may not allocate ---------------------------------------------------------------
+// lookm_decode_attention_noalloc keeps the partial results of its two kernels in this array instead of a
+// caller's workspace.  Every GPU the library runs on holds its own copy, at its own address, until the process
+// ends.  In host code the array's name is only a stand-in for the symbol: the device address is asked for once per
+// device (with that device current) and kept; kernels get that pointer as their argument, exactly as they get the
+// caller's workspace in lookm_decode_attention.  Nothing in the array has to start at zero: the first kernel writes
+// every partial the second one reads.
+static __device__ __align__(256) unsigned char scratch[LOOKM_DECODE_NOALLOC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mutex;
+static float* g_scratch_ptr[64];     // per device; null until resolved
+
+int decode_static_scratch_setup()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LOOKM_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] != nullptr) return LOOKM_OK;
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return LOOKM_ERR_DEVICE;
+    g_scratch_ptr[dev] = static_cast<float*>(ptr);
+    return LOOKM_OK;
+}
+
+// the current device's copy of the array, or null when decode_static_scratch_setup has not succeeded on it
+float* decode_static_scratch()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    return g_scratch_ptr[dev];
 }
 
 }  // namespace lookm_host

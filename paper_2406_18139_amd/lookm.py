@@ -34,7 +34,7 @@ EXPORTS = ["lookm_version", "lookm_status_string", "lookm_protected_count", "loo
            "lookm_compress_profile", "lookm_scores_lse", "lookm_compress_lse", "lookm_budget_from_ratios",
            "lookm_select_rule_", "lookm_compress_batch", "lookm_scores_window", "lookm_job_profile", "lookm_decode_workspace_bytes",
            "lookm_decode_attention", "lookm_scores_grouped", "lookm_probe_mfma", "lookm_init",
-           "lookm_compress_batch_two_streams", "lookm_workspace_offset"]
+           "lookm_compress_batch_two_streams", "lookm_workspace_offset", "lookm_decode_attention_noalloc"]
 
 KERNELS = ["score_lse", "score_lse_fold", "score_colsum", "score_colsum_fold", "select", "rnorm", "nearest",
            "nearest_fold", "bucket", "merge"]   # LOOKM_K_* order
@@ -106,6 +106,8 @@ def lib() -> ctypes.CDLL:
         L.lookm_decode_workspace_bytes.argtypes = [I, I]
         L.lookm_decode_attention.restype = I
         L.lookm_decode_attention.argtypes = [vp, vp, vp, I, I, I, I, I, vp, vp, sz, vp]
+        L.lookm_decode_attention_noalloc.restype = I
+        L.lookm_decode_attention_noalloc.argtypes = [vp, vp, vp, I, I, I, I, I, vp, vp]
         L.lookm_job_profile.restype = I
         L.lookm_job_profile.argtypes = [ctypes.POINTER(Job), I, ctypes.POINTER(ctypes.c_float), vp]
         L.lookm_compress_batch.restype = I
@@ -352,6 +354,18 @@ def lookm_decode_attention(q, k_cache, v_cache, S: Optional[int] = None, out: Op
                                       dt, _dev(out, "out"), wp, wn, _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_decode_attention")
+    return out
+
+
+def lookm_decode_attention_noalloc(q, k_cache, v_cache, out: torch.Tensor, S: Optional[int] = None) -> torch.Tensor:
+    """lookm_decode_attention_noalloc: the same step with the library's static scratch; ``out`` ([H, d], the inputs'
+    dtype) is the caller's, nothing is allocated here or in the library."""
+    H, rows, d = k_cache.shape
+    S = rows if S is None else int(S)
+    rc = lib().lookm_decode_attention_noalloc(_dev(q, "q"), _dev(k_cache, "k_cache"), _dev(v_cache, "v_cache"), H, rows,
+                                              S, d, _dt(q), _dev(out, "out"), _stream())
+    if rc != OK:
+        raise LookmError(rc, "lookm_decode_attention_noalloc")
     return out
 
 

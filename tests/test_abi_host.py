@@ -181,6 +181,21 @@ def test_decode_rejects_bad_arguments():
     assert call(wsn=16) == lookm.ERR_WORKSPACE and call(ws=None) == lookm.ERR_WORKSPACE
 
 
+def test_noalloc_decode_rejects_bad_arguments_and_sizes_beyond_its_scratch():
+    L = lookm.lib()
+    def call(**kw):
+        a = dict(q=FAKE, k=FAKE, v=FAKE, H=2, rows=64, S=64, d=64, dt=0, out=FAKE, st=None)
+        a.update(kw)
+        return L.lookm_decode_attention_noalloc(*[a[n] for n in ("q", "k", "v", "H", "rows", "S", "d", "dt", "out", "st")])
+
+    assert call(out=None) == lookm.ERR_INVALID_ARG
+    assert call(S=65) == lookm.ERR_INVALID_ARG and call(dt=2) == lookm.ERR_INVALID_ARG
+    assert call(d=12) == lookm.ERR_UNSUPPORTED
+    assert call(k=FAKE + 2) == lookm.ERR_INVALID_ARG
+    # 64 heads x 256 pieces x (256 + 2) floats = 16.9 MB of partial results: more than the 8 MiB the library holds
+    assert call(H=64, rows=100000, S=100000, d=256, dt=1) == lookm.ERR_WORKSPACE
+
+
 def test_probe_rejects_bad_arguments():
     import ctypes
     L = lookm.lib()
