@@ -28,6 +28,24 @@ PEAK_MFMA_BF16 = 2.5e15   # dense bf16 MFMA, FLOP/s
 PEAK_HBM = 8.0e12         # B/s
 
 
+PREWARM_SECONDS = 0.3     # untimed calls before the counted warm-up, sized by time
+
+
+def prewarm(step, seconds: float = PREWARM_SECONDS):
+    """Runs ``step`` until ``seconds`` of wall-clock have passed (at least 3 calls): after an idle period the GPU
+    needs some tens of milliseconds under load before its clocks settle, whatever warm-up count the caller asked for.
+    Returns (calls, milliseconds)."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    n = 0
+    while n < 3 or time.perf_counter() - t0 < seconds:
+        for _ in range(4):
+            step()
+        torch.cuda.synchronize()
+        n += 4
+    return n, (time.perf_counter() - t0) * 1e3
+
+
 def algorithmic_work(w: W.Workload, score_window: int = 0) -> dict:
     """Work the method needs per launch of each kernel (all heads of one layer); nothing a particular
     tiling adds (masked halves of diagonal tiles, padding, re-reads) is counted."""
@@ -65,14 +83,17 @@ def stack(args) -> int:
         per_prompt.append([(w, B, *W.generate_on_device(w, layer, dev), out, ws) for layer in range(layers)])
     # Layer-major order, as a prefill produces the caches: layer 0 of every prompt, then layer 1, ...  The layers of a
     # prompt share its workspace and outputs and therefore run in order; different prompts are independent, and the
-    # library runs them on two lanes (see lookm_compress_batch).
+    # library alternates them between the two streams it is given (see lookm_compress_batch_two_streams).
     jobs = [per_prompt[p][layer] for layer in range(layers) for p in range(len(prompts))]
     torch.cuda.synchronize()
     batch = [lookm.make_job(q, k, v, mask, B, w.M, "weighted", out, ws) for w, B, q, k, v, mask, out, ws in jobs]
 
-    def step():
-        lookm.lookm_compress_batch(batch)
+    aux = torch.cuda.Stream() if args.two_streams else None
 
+    def step():
+        lookm.lookm_compress_batch(batch, aux_stream=aux)
+
+    prewarm_calls, prewarm_ms = prewarm(step, 0.2)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -85,17 +106,44 @@ def stack(args) -> int:
     if any(bad):
         print(f"bench.py: device status {bad}", file=sys.stderr)
         return 1
+    # Roofline: the score passes are 87 % of the stack's arithmetic.  Per-kernel durations of one job per prompt
+    # (layer 0) come from HIP events recorded by the library on the launch stream; the dominant kernel of the stack
+    # is the first score pass of the longest prompt.
+    score_flop = sum(2 * 2.0 * w.d * (w.L * (w.L + 1) // 2) * w.H for w in prompts) * layers
+    per_prompt_kernels = {}
+    dom = None
+    for pi, w in enumerate(prompts):
+        kms = lookm.lookm_job_profile(batch[pi], 5)
+        kms.pop("rnorm", None)
+        per_prompt_kernels[w.name] = {k_: round(v_, 5) for k_, v_ in kms.items()}
+        name = max(kms, key=kms.get)
+        if dom is None or kms[name] > dom[2]:
+            dom = (w, name, kms[name])
+    dw, dname, dms = dom
+    dwork = algorithmic_work(dw)[dname]
+    dach = dwork[1] / (dms * 1e-3)
+    dpeak = PEAK_MFMA_BF16 if dwork[0] == "mfma" else PEAK_HBM
+    roofline = {"kernel": f"{dname} of prompt {dw.name} (L={dw.L})", "bound": dwork[0],
+                "achieved": round(dach / (1e12 if dwork[0] == "mfma" else 1e9), 3),
+                "peak": dpeak / (1e12 if dwork[0] == "mfma" else 1e9),
+                "unit": "TFLOP/s" if dwork[0] == "mfma" else "GB/s", "frac": round(dach / dpeak, 4), "traffic": None,
+                "score_passes_whole_stack": {"flop": score_flop,
+                                             "frac_mfma_peak_over_step_time": round(score_flop / (ms * 1e-3) / PEAK_MFMA_BF16, 4)}}
     tokens = sum(w.L for w in prompts)
     per_token = layers * prompts[0].H * prompts[0].d * 2 * 2          # K and V, bf16, all layers and heads
     total_b = tokens * per_token
     saved_b = sum(w.L - w.budget() for w in prompts) * per_token
     print(json.dumps({
         "metric": "compression time of the full stack (32 layers x 4 ragged prompts)", "value": round(ms, 3), "unit": "ms",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": False,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "prewarm": {"calls": prewarm_calls, "ms": round(prewarm_ms, 1)}, "ms_per_step": round(ms, 3),
+        "higher_is_better": False,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic (drawn on the GPU)",
         "config": {"workload": "stack: 32 layers x 32 heads x d128 bf16, prompts of "
                                + ", ".join(str(w.L) for w in prompts) + " tokens, budgets "
-                               + ", ".join(str(w.budget()) for w in prompts) + ", recent_window 32, merge=weighted"},
+                               + ", ".join(str(w.budget()) for w in prompts) + ", recent_window 32, merge=weighted",
+                   "streams": 2 if args.two_streams else 1},
+        "roofline": roofline, "kernels_ms_layer0": per_prompt_kernels,
         "tokens_per_s_all_layers": round(tokens * layers / (ms * 1e-3), 1),
         "cache_bytes": total_b, "cache_bytes_after": total_b - saved_b, "cache_bytes_saved": saved_b,
         "fraction_saved": round(saved_b / total_b, 4)}))
@@ -171,6 +219,8 @@ def main() -> int:
                     help="supply the prefill's row log-sum-exp (lookm_compress_lse): the first score pass is skipped")
     ap.add_argument("--score-window", type=int, default=0,
                     help="variant: scores from the last W query rows only (lookm_scores_window), via a lookm_job")
+    ap.add_argument("--one-stream", dest="two_streams", action="store_false",
+                    help="--workload stack: enqueue all jobs on one stream (default: lookm_compress_batch_two_streams)")
     ap.add_argument("--split-heads", type=int, default=0,
                     help="issue the layer as this many jobs over equal groups of heads through ONE "
                          "lookm_compress_batch_two_streams call (0: one lookm_compress call on one stream)")
@@ -269,6 +319,7 @@ def main() -> int:
         else:
             lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, out=out, workspace=ws, check=False)
 
+    prewarm_calls, prewarm_ms = prewarm(step)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -307,16 +358,21 @@ def main() -> int:
     dach = damount / (kms[dominant] * 1e-3)
     # HBM bytes per launch of that kernel, from the committed rocprofv3 --pmc summary (scaled by the copy
     # calibration); None when no summary covers this workload / kernel
-    traffic = None
+    traffic, traffic_source = None, None
     tfile = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"hbm_traffic_{w.name}.json")
-    if os.path.exists(tfile):
+    if os.path.exists(tfile) and not variant and split_jobs is None:
         with open(tfile) as f:
-            traffic = json.load(f).get("bytes_per_launch", {}).get(dominant)
+            stored = json.load(f)
+        traffic = stored.get("bytes_per_launch", {}).get(dominant)
+        if traffic is not None:
+            traffic_source = (f"stored counter figure, not of this run: profiles/hbm_traffic_{w.name}.json "
+                              f"({stored.get('measured', 'date not recorded')}; rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE, "
+                              "scaled by the copy calibration)")
     roofline = {"kernel": dominant, "bound": dbound,
                 "achieved": round(dach / (1e12 if dbound == "mfma" else 1e9), 3),
                 "peak": dpeak / (1e12 if dbound == "mfma" else 1e9),
                 "unit": "TFLOP/s" if dbound == "mfma" else "GB/s",
-                "frac": round(dach / dpeak, 4), "traffic": traffic}
+                "frac": round(dach / dpeak, 4), "traffic": traffic, "traffic_source": traffic_source}
     score_ms = kms.get("score_lse", 0.0) + kms.get("score_lse_fold", 0.0) + kms["score_colsum"] + kms["score_colsum_fold"]
     smc_ms = kms["select"] + kms["bucket"] + kms["merge"]
     smc_bytes = work["select"][1] + work["bucket"][1] + work["merge"][1]
@@ -361,6 +417,8 @@ def main() -> int:
         "value": round(w.L / (ms_per_step * 1e-3), 1),
         "unit": "tokens/s/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "prewarm": {"calls": prewarm_calls, "ms": round(prewarm_ms, 1),
+                    "what": "untimed calls before the counted warm-up, until the clocks have settled"},
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",

@@ -56,14 +56,20 @@ typedef enum {
     LOOKM_ERR_DEVICE = -6                  /* a HIP runtime call failed */
 } lookm_status;
 
+/* Every enumeration that is an ARGUMENT carries two range markers (never valid values): they make each int a
+ * representable value of the type, so that a caller's out-of-range value reaches the library's validation
+ * (LOOKM_ERR_INVALID_ARG) instead of being undefined behaviour in a C++ translation unit. */
+#define LOOKM_ENUM_RANGE_(prefix) prefix##_RANGE_LO_ = -0x7fffffff - 1, prefix##_RANGE_HI_ = 0x7fffffff
+
 typedef enum {
     LOOKM_MERGE_NONE = 0,     /* eviction only: outputs are exact gathers of the conserved rows */
     LOOKM_MERGE_AVERAGED = 1, /* Eq. 10 */
     LOOKM_MERGE_PIVOTAL = 2,  /* Eq. 11 */
-    LOOKM_MERGE_WEIGHTED = 3  /* Eq. 12 (taken literally: divisor n+1, weights = matching cosines) */
+    LOOKM_MERGE_WEIGHTED = 3, /* Eq. 12 (taken literally: divisor n+1, weights = matching cosines) */
+    LOOKM_ENUM_RANGE_(LOOKM_MERGE)
 } lookm_merge_mode;
 
-typedef enum { LOOKM_F32 = 0, LOOKM_BF16 = 1 } lookm_dtype;
+typedef enum { LOOKM_F32 = 0, LOOKM_BF16 = 1, LOOKM_ENUM_RANGE_(LOOKM_DTYPE) } lookm_dtype;
 
 typedef enum {
     /* text tokens and the recent window are always conserved; a budget below |T u R| is an error */
@@ -72,7 +78,8 @@ typedef enum {
      * places before the window go to the highest boosted scores; when they cannot hold every text token, the
      * text tokens compete for them by score and no image token is conserved.  Same result as
      * LOOKM_SELECT_PROTECT_TEXT whenever that rule accepts the budget. */
-    LOOKM_SELECT_LITERAL = 1
+    LOOKM_SELECT_LITERAL = 1,
+    LOOKM_ENUM_RANGE_(LOOKM_SELECT)
 } lookm_select_rule;
 
 /* Library version string, static storage. */
@@ -326,7 +333,8 @@ int lookm_decode_attention_noalloc(const void* q, const void* k_cache, const voi
 typedef enum {
     LOOKM_WS_EVICTED = 0,   /* int32 [kv_heads, L - budget], ascending positions */
     LOOKM_WS_ASSIGN = 1,    /* int32 [kv_heads, L - budget], slot of the matched conserved key */
-    LOOKM_WS_SIM = 2        /* float [kv_heads, L - budget], the matching cosine */
+    LOOKM_WS_SIM = 2,       /* float [kv_heads, L - budget], the matching cosine */
+    LOOKM_ENUM_RANGE_(LOOKM_WS)
 } lookm_workspace_item;
 
 /*

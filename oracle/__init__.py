@@ -40,6 +40,18 @@ def build(force: bool = False) -> Path:
     return _LIB
 
 
+def build_sanitized() -> Path:
+    """The oracle with AddressSanitizer and UndefinedBehaviorSanitizer (oracle/_build/liblookm_oracle_san.so), for the
+    test that runs the pins against it; load it through LOOKM_ORACLE_LIB with gcc's libasan preloaded."""
+    out_dir = _HERE / "_build"
+    out_dir.mkdir(exist_ok=True)
+    out = out_dir / "liblookm_oracle_san.so"
+    subprocess.check_call(["gcc", "-O1", "-g", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", str(_SRC), "-o", str(out),
+                           "-lm"])
+    return out
+
+
 _lib = None
 
 

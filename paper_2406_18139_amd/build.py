@@ -37,6 +37,40 @@ def _compile(src: str) -> Path:
     return obj
 
 
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+             "-fno-sanitize-recover=undefined"]
+
+
+def build_host_sanitized() -> Path:
+    """The same library with AddressSanitizer and UndefinedBehaviorSanitizer on its HOST code only (argument
+    validation, workspace layout, launch sequencing; device code is compiled as usual), for the CPU-side tests:
+    paper_2406_18139_amd/_build/liblookm_san.so.  Load it with the clang runtime preloaded (see asan_runtime)."""
+    OBJ.mkdir(exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        obj = OBJ / (src + ".san.o")
+        flags = [f for f in FLAGS if f != "-O3"] + ["-O1", "-g"]
+        p = subprocess.run([HIPCC, *flags, *SAN_FLAGS, "-c", str(CSRC / src), "-o", str(obj)], capture_output=True, text=True)
+        if p.returncode != 0:
+            raise RuntimeError(f"hipcc (sanitized) failed for {src}:\n{p.stderr}")
+        objs.append(obj)
+    out = OBJ / "liblookm_san.so"
+    subprocess.check_call([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *SAN_FLAGS, *map(str, objs), "-o", str(out)])
+    return out
+
+
+def asan_runtime() -> Path:
+    """The shared AddressSanitizer runtime of the clang that hipcc drives (to be preloaded into the Python process)."""
+    p = subprocess.run([HIPCC, "-print-file-name=libclang_rt.asan-x86_64.so"], capture_output=True, text=True)
+    path = Path(p.stdout.strip())
+    if not path.is_absolute() or not path.exists():
+        cands = sorted(Path("/opt/rocm/lib/llvm/lib/clang").glob("*/lib/linux/libclang_rt.asan-x86_64.so"))
+        if not cands:
+            raise FileNotFoundError("libclang_rt.asan-x86_64.so not found")
+        path = cands[-1]
+    return path
+
+
 def build(verbose: bool = True) -> Path:
     OBJ.mkdir(exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:

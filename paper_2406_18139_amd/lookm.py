@@ -14,8 +14,11 @@ from typing import Optional
 
 import torch
 
+import os
+
 _PKG = Path(__file__).resolve().parent
-LIB_PATH = _PKG / "liblookm.so"
+# LOOKM_LIB: another build of the same library (the host-sanitizer build the CPU tests make); default: the in-tree one
+LIB_PATH = Path(os.environ["LOOKM_LIB"]) if os.environ.get("LOOKM_LIB") else _PKG / "liblookm.so"
 
 OK = 0
 ERR_INVALID_ARG = -1
