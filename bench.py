@@ -46,18 +46,24 @@ def prewarm(step, seconds: float = PREWARM_SECONDS):
     return n, (time.perf_counter() - t0) * 1e3
 
 
-def algorithmic_work(w: W.Workload, score_window: int = 0) -> dict:
+def algorithmic_work(w: W.Workload, score_window: int = 0, all_scores: bool = True) -> dict:
     """Work the method needs per launch of each kernel (all heads of one layer); nothing a particular
-    tiling adds (masked halves of diagonal tiles, padding, re-reads) is counted."""
+    tiling adds (masked halves of diagonal tiles, padding, re-reads) is counted.  ``all_scores`` False: the caller
+    does not ask for the scores themselves, so pass 2 only owes the scores of the keys that compete in the selection
+    (image tokens before the recent window, Eq. 5-8)."""
     H, L, d, B = w.H, w.L, w.d, w.budget()
     Le = L - B
     e = 2 if w.dtype == "bf16" else 4
     r0 = L - score_window if score_window > 0 else 0
     pairs = L * (L + 1) // 2 - r0 * (r0 + 1) // 2          # causal pairs of the query rows that count
+    pairs2 = pairs                                         # pairs pass 2 owes
+    if not all_scores and w.dtype == "bf16" and d == 128:
+        m = w.mask()
+        pairs2 = sum(L - max(j, r0) for j in range(L - w.M) if m[j] == 1)
     return {
         "score_lse": ("mfma", 2.0 * d * pairs * H),
         "score_lse_fold": ("hbm", H * 4.0 * L * 3),        # two partials in, one value out (at least one chunk)
-        "score_colsum": ("mfma", 2.0 * d * pairs * H),
+        "score_colsum": ("mfma", 2.0 * d * pairs2 * H),
         "score_colsum_fold": ("hbm", H * 4.0 * L * 2),
         "select": ("hbm", H * (4.0 * L + 4.0 * B + 4.0 * Le) + L),
         "rnorm": ("hbm", H * (L * d * e + 4.0 * L)),
@@ -109,7 +115,10 @@ def stack(args) -> int:
     # Roofline: the score passes are 87 % of the stack's arithmetic.  Per-kernel durations of one job per prompt
     # (layer 0) come from HIP events recorded by the library on the launch stream; the dominant kernel of the stack
     # is the first score pass of the longest prompt.
-    score_flop = sum(2 * 2.0 * w.d * (w.L * (w.L + 1) // 2) * w.H for w in prompts) * layers
+    score_flop = 0.0
+    for w in prompts:                      # pass 1 over all pairs, pass 2 over the competing keys' pairs (no scores_out)
+        wk = algorithmic_work(w, all_scores=False)
+        score_flop += (wk["score_lse"][1] + wk["score_colsum"][1]) * layers
     per_prompt_kernels = {}
     dom = None
     for pi, w in enumerate(prompts):
@@ -120,7 +129,7 @@ def stack(args) -> int:
         if dom is None or kms[name] > dom[2]:
             dom = (w, name, kms[name])
     dw, dname, dms = dom
-    dwork = algorithmic_work(dw)[dname]
+    dwork = algorithmic_work(dw, all_scores=False)[dname]
     dach = dwork[1] / (dms * 1e-3)
     dpeak = PEAK_MFMA_BF16 if dwork[0] == "mfma" else PEAK_HBM
     roofline = {"kernel": f"{dname} of prompt {dw.name} (L={dw.L})", "bound": dwork[0],
@@ -221,6 +230,9 @@ def main() -> int:
                     help="variant: scores from the last W query rows only (lookm_scores_window), via a lookm_job")
     ap.add_argument("--one-stream", dest="two_streams", action="store_false",
                     help="--workload stack: enqueue all jobs on one stream (default: lookm_compress_batch_two_streams)")
+    ap.add_argument("--with-scores", action="store_true",
+                    help="also return the scores A_s of every key (scores_out): the second score pass then runs over "
+                         "all keys, not only over the image tokens that compete in the selection")
     ap.add_argument("--split-heads", type=int, default=0,
                     help="issue the layer as this many jobs over equal groups of heads through ONE "
                          "lookm_compress_batch_two_streams call (0: one lookm_compress call on one stream)")
@@ -275,7 +287,7 @@ def main() -> int:
     q, k, v, mask = W.generate(w)
     dev = torch.device("cuda:0")
     qg, kg, vg, mg = (t.to(dev) for t in (q, k, v, mask))
-    out = lookm.alloc_outputs(w.H, w.L, w.d, B, qg.dtype, dev)
+    out = lookm.alloc_outputs(w.H, w.L, w.d, B, qg.dtype, dev, want_scores=args.with_scores)
     ws = lookm.alloc_workspace(w.H, w.L, w.d, B, lookm.BF16 if w.dtype == "bf16" else lookm.F32, dev)
 
     row_lse = None
@@ -336,7 +348,7 @@ def main() -> int:
 
     # per-kernel durations: HIP events recorded by the library on the launch stream, same inputs
     kms = lookm.lookm_job_profile(job, max(min(args.steps, 30), 1))
-    work = algorithmic_work(w, args.score_window)
+    work = algorithmic_work(w, args.score_window, all_scores=args.with_scores)
     if args.reuse_lse:
         kms.pop("score_lse"), kms.pop("score_lse_fold")          # not launched: the prefill's values are used
     kernels = {}

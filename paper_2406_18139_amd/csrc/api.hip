@@ -14,7 +14,7 @@ constexpr size_t kAlign = 256;
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t lse, scores, evicted, assign, sim, rnorm, plan, member_pos, member_w, partials, total;
+    size_t lse, scores, evicted, assign, sim, rnorm, plan, member_pos, member_w, lists, partials, total;
 };
 
 // Hq query heads, H key / value heads (Hq = H without grouped query heads): only the row log-sum-exp and the score
@@ -33,6 +33,7 @@ Layout make_layout(int Hq, int H, int L, int d, int dt, int budget)
     w.plan = o;    o += align_up((size_t)H * budget * 4 * sizeof(int32_t));   // merge plan, one int4 per slot
     w.member_pos = o; o += align_up(HE * sizeof(int32_t));
     w.member_w = o;   o += align_up(HE * sizeof(float));
+    w.lists = o;      o += align_up(lookm_host::score_list_ints(L) * sizeof(int32_t));   // competing / protected keys
     // the score partials and the matching partials are never live at the same time: one slice serves both
     w.partials = o;
     o += align_up(std::max(lookm_host::scores_scratch_floats(Hq, L, d, (lookm_dtype)dt) * sizeof(float),
@@ -287,7 +288,7 @@ static int scores_impl(const void* q, const void* k, const float* row_lse, int H
     const Layout w = make_layout(H, kv_heads, L, d, (int)dt, 0);
     if ((rc = lookm_host::ensure_device_ready()) != LOOKM_OK) return rc;
     return lookm_host::launch_scores(q, k, H, kv_heads, L, d, dt, window ? L - window : 0, at<float>(workspace, w.lse),
-                                     row_lse, scores_out, nullptr, at<float>(workspace, w.partials),
+                                     row_lse, scores_out, nullptr, at<float>(workspace, w.partials), nullptr, 0, nullptr,
                                      (hipStream_t)hip_stream);
 }
 
@@ -432,9 +433,14 @@ int enqueue_job(const lookm_job& j, hipStream_t st)
     // the matching needs the inverse key norms; the matrix-core score pass writes them from the key rows it holds
     const bool match = j.merge_mode != LOOKM_MERGE_NONE && budget < L && budget > 0;
     float* rnorm = at<float>(workspace, w.rnorm);
+    // Only the image tokens before the window compete for places (Eq. 5-8): when the caller does not ask for the
+    // scores themselves and every text token is protected, the other keys' scores are never looked at
+    const bool competing_only = j.scores_out == nullptr && j.rule == LOOKM_SELECT_PROTECT_TEXT;
     int rc = lookm_host::launch_scores(j.q, j.k, Hq, H, L, d, dt, j.score_window ? L - j.score_window : 0,
                                        at<float>(workspace, w.lse), j.row_lse, scores,
-                                       match ? rnorm : nullptr, at<float>(workspace, w.partials), st);
+                                       match ? rnorm : nullptr, at<float>(workspace, w.partials),
+                                       competing_only ? j.modality_mask : nullptr, j.recent_window,
+                                       competing_only ? at<int32_t>(workspace, w.lists) : nullptr, st);
     if (rc != LOOKM_OK) return rc;
     rc = lookm_host::launch_select(scores, j.modality_mask, H, L, budget, j.recent_window, (int)j.rule, j.kept_idx,
                                    evicted, j.status_out, st);

@@ -79,8 +79,14 @@ namespace lookm_host {
 // first_row: only the query rows first_row .. L-1 are summed (0 = all rows, Eq. 4 as printed)
 // H query heads in groups of H / kv_heads that read one key head each (kv_heads = H: plain multi-head attention);
 // lse, lse_in: [H, L]; scores, rnorm: [kv_heads, L]
+// mask, M, lists (all or none): the caller only needs the scores of the keys that compete in the selection (image
+// tokens before the recent window); the matrix-core path then skips the other keys in pass 2 and leaves their
+// entries of `scores` unwritten (the portable path computes every score regardless).  lists: device scratch of
+// score_list_ints(L) ints.
 int launch_scores(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt, int first_row,
-                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st);
+                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, const uint8_t* mask, int M,
+                  int32_t* lists, hipStream_t st);
+inline size_t score_list_ints(int L) { return (size_t)2 * L + 64; }
 inline bool scores_write_rnorm(int d, lookm_dtype dt) { return dt == LOOKM_BF16 && d == 128; }
 size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt);
 int launch_select(const float* scores, const uint8_t* mask, int H, int L, int budget, int M, int rule, int32_t* kept,

@@ -161,7 +161,8 @@ __global__ void __launch_bounds__(256) k_score_colsum_generic(const T* __restric
 namespace lookm_host {
 
 int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L, int d, int R0, float* lse,
-                       const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st);
+                       const float* lse_in, float* scores, float* rnorm, float* scratch, const uint8_t* mask, int M,
+                       int32_t* lists, hipStream_t st);
 size_t scores_mfma_scratch_floats(int H, int L);
 
 template <typename T>
@@ -205,12 +206,13 @@ size_t scores_scratch_floats(int H, int L, int d, lookm_dtype dt)
 }
 
 int launch_scores(const void* q, const void* k, int H, int kv_heads, int L, int d, lookm_dtype dt, int first_row,
-                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
+                  float* lse, const float* lse_in, float* scores, float* rnorm, float* scratch, const uint8_t* mask, int M,
+                  int32_t* lists, hipStream_t st)
 {
     const int R0 = first_row;
     if (dt == LOOKM_BF16) {
         if (scores_write_rnorm(d, dt))
-            return launch_scores_mfma(q, k, H, kv_heads, L, d, R0, lse, lse_in, scores, rnorm, scratch, st);
+            return launch_scores_mfma(q, k, H, kv_heads, L, d, R0, lse, lse_in, scores, rnorm, scratch, mask, M, lists, st);
         return launch_scores_generic((const lookm::bf16_t*)q, (const lookm::bf16_t*)k, H, kv_heads, L, d, R0, lse, lse_in,
                                      scores, st);
     }

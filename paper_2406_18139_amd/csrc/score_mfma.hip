@@ -133,11 +133,52 @@ __host__ __device__ inline int strip_chunks(int pass, int t, int L, int CT, int 
 //   PASS 2 writes part_a = partial column sum per (chunk, stationary row).  Its stationary rows are keys: when
 //   `rnorm` is given, the workgroup of a strip's first chunk also writes rnorm[h, j] = 1 / ||k_j|| (0 for a
 //   zero key) for the matching of Eq. 9, from the registers it holds anyway - the keys are not read again for it.
-template <int PASS>
+// ---- scores for the competing keys only -------------------------------------------------------------------
+// Selection ranks only the image tokens before the recent window (Eq. 5-8: text tokens and the window are
+// conserved whatever their score).  When the caller does not ask for the scores themselves, pass 2 therefore
+// runs over those keys alone: its strips are 256 consecutive entries of the ascending list of competing positions
+// instead of 256 consecutive positions, and everything else - chunk boundaries, the tiles a key's column sum runs
+// over, the order of every addition - is unchanged, so the scores of the competing keys come out bit for bit as
+// on the dense path.  The lists are built from the modality mask by one extra workgroup of pass 1 (or by a small
+// kernel of its own when pass 1 is skipped):
+//   lists[0] = number of competing keys, lists[1] = number of protected keys,
+//   lists[LIST_HEAD .. +L) competing positions ascending, lists[LIST_HEAD + L .. +L) protected positions ascending.
+constexpr int LIST_HEAD = 64;
+
+__device__ __forceinline__ void build_key_lists(const uint8_t* __restrict__ mask, int L, int M, int32_t* __restrict__ lists,
+                                                int* scan /* LDS, 256 ints */)
+{
+    const int tid = threadIdx.x, per = (L + 255) / 256, lo = min(L, tid * per), hi = min(L, lo + per);
+    int nc = 0;
+    for (int j = lo; j < hi; ++j) nc += (mask[j] != 0 && j < L - M) ? 1 : 0;
+    scan[tid] = nc;
+    __syncthreads();
+    for (int off = 1; off < 256; off <<= 1) {          // inclusive scan of the competing counts
+        const int v = (tid >= off) ? scan[tid - off] : 0;
+        __syncthreads();
+        scan[tid] += v;
+        __syncthreads();
+    }
+    int c_at = scan[tid] - nc, p_at = lo - c_at;       // competing / protected keys before this thread's range
+    if (tid == 255) { lists[0] = scan[255]; lists[1] = L - scan[255]; }
+    for (int j = lo; j < hi; ++j) {
+        if (mask[j] != 0 && j < L - M) lists[LIST_HEAD + c_at++] = j;
+        else lists[LIST_HEAD + L + p_at++] = j;
+    }
+}
+
+__global__ void __launch_bounds__(256) k_score_lists(const uint8_t* __restrict__ mask, int L, int M, int32_t* __restrict__ lists)
+{
+    __shared__ int scan[256];
+    build_key_lists(mask, L, M, lists, scan);
+}
+
+template <int PASS, bool SPARSE>
 __global__ void __launch_bounds__(256, 3)
 k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, int group, int L, int R0, float scale2,
              int C, int U, const float* __restrict__ lse2, float lse_scale, float* __restrict__ part_a,
-             float* __restrict__ part_b, float* __restrict__ rnorm)
+             float* __restrict__ part_b, float* __restrict__ rnorm, const uint8_t* __restrict__ modality, int M,
+             int32_t* __restrict__ lists)
 {
     // Two tiles as separate arrays, with the buffer of a tile known at compile time (the tile loop is unrolled by
     // two): the compiler then sees that a fragment read of one array cannot alias the loads in flight to the
@@ -147,6 +188,18 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     __shared__ __attribute__((aligned(16))) bf16_t xs1[BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl0[BX];   // pass 2: -lse2[i] of the streamed query rows
     __shared__ __attribute__((aligned(16))) float xl1[BX];
+    __shared__ int spos[SPARSE ? 2 * 256 : 1];   // sparse pass 2: positions of every lane's two stationary rows
+
+    // pass 1 with a mask: the launch has one workgroup more, which builds the key lists for pass 2
+    if (PASS == 1 && modality != nullptr && blockIdx.x == gridDim.x - 1) {
+        build_key_lists(modality, L, M, lists, reinterpret_cast<int*>(xs0));
+        return;
+    }
+    // pass 2 with lists: stationary rows are entries of the list of competing positions
+    static_assert(PASS == 2 || !SPARSE, "only pass 2 has a sparse form");
+    constexpr bool sparse = SPARSE;
+    const int NC = sparse ? lists[0] : L;                 // stationary rows in all
+    const int32_t* clist = lists + LIST_HEAD;
 
     // Consecutive workgroup ids go to consecutive XCDs.  With 8 or more heads, XCD x works through heads
     // x, x+8, ... one at a time, so its L2 holds one head's current chunk; with fewer heads each head
@@ -189,11 +242,37 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
               n = lane & 31;
     const int w0 = s0 + wave * 64;
 
-    // stationary fragments: lane holds row (w0 + cb*32 + n), dims ks*16 + half*8 .. +7
+    // The strip's first row decides where its streamed range starts (sparse: a list entry).
+    const int p_strip = !sparse ? s0 : (s0 < NC) ? __builtin_amdgcn_readfirstlane(clist[min(s0, L - 1)]) : 0;
+    const int strip_begin = (PASS == 1) ? 0 : (p_strip / BX) * BX;
+    const int strip_end = (PASS == 1) ? min(L, s0 + BS) : L;
+    const int x_begin = max(max(strip_begin, g * CT), (PASS == 2) ? (R0 / BX) * BX : 0);   // tile-aligned
+    const int x_end = min(strip_end, (g + 1) * CT);
+    // (sparse) no such strip of competing keys, or the chunk ends before the strip's first key: such a unit runs no
+    // tile and writes partials that nothing reads (an early exit here costs the kernel its register budget)
+    const bool idle = sparse && (s0 >= NC || x_end <= x_begin);
+
+    // Positions of this lane's two stationary rows (cb = 0, 1) and of the wave's first and last row: row numbers
+    // themselves on the dense path, list entries on the sparse one (rows past the end of the list: a position past
+    // the prompt, which no query row reaches).
+    int sA = w0 + n, sB = w0 + 32 + n, p_wave_lo = w0, p_wave_hi = w0 + 63;
+    if (sparse) {
+        sA = (w0 + n < NC) ? clist[w0 + n] : 0x3fffffff;
+        sB = (w0 + 32 + n < NC) ? clist[w0 + 32 + n] : 0x3fffffff;
+        // wave-uniform values: kept in scalar registers
+        p_wave_lo = (w0 < NC) ? __builtin_amdgcn_readfirstlane(clist[min(w0, NC - 1)]) : 0x3fffffff;
+        p_wave_hi = (w0 < NC) ? __builtin_amdgcn_readfirstlane(clist[min(w0 + 63, NC - 1)]) : 0x3fffffff;
+        // the per-lane positions are only needed again where a tile touches the diagonal: parked in LDS meanwhile
+        // (each lane reads back what it wrote itself, so no barrier is involved)
+        spos[tid] = sA;
+        spos[256 + tid] = sB;
+    }
+
+    // stationary fragments: lane holds row sA / sB, dims ks*16 + half*8 .. +7
     bf16x8 sf[2][8];
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb) {
-        const int row = w0 + cb * 32 + n;
+        const int row = cb ? sB : sA;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
@@ -202,11 +281,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         }
     }
 
-    const int strip_begin = (PASS == 1) ? 0 : s0;
-    const int strip_end = (PASS == 1) ? min(L, s0 + BS) : L;
-    const int x_begin = max(max(strip_begin, g * CT), (PASS == 2) ? (R0 / BX) * BX : 0);   // tile-aligned
-    const int x_end = min(strip_end, (g + 1) * CT);
-    const int n_it = (x_end - x_begin + BX - 1) / BX;
+    const int n_it = idle ? 0 : (x_end - x_begin + BX - 1) / BX;
 
     // Staging goes from global memory straight into LDS (global_load_lds_dwordx4): the 64 lanes of a wave
     // fill 1 KB = 4 consecutive LDS rows, lane l landing at chunk l%16 of row l/16, so the swizzle is applied
@@ -256,11 +331,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
     float run[2] = {0.f, 0.f};                          // pass 2 state
-    const int sA = w0 + n, sB = w0 + 32 + n;            // stationary index of this lane for cb = 0, 1
 
     load_tile(x_begin, xs0);
     store_tile(xl0, x_begin);
-    if (PASS == 2 && rnorm != nullptr && g == first_chunk(2, tile, CT, R0) && h % group == 0) {
+    if (PASS == 2 && rnorm != nullptr && g == max(strip_begin, (R0 / BX) * BX) / CT && h % group == 0) {
         // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
         // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
         // partial sums, number p over groups p and p + 8, then a pairwise tree), so both give the same bits
@@ -288,7 +362,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 #pragma unroll
             for (int j = 0; j < 4; ++j) pair[j] = part[j] + __shfl_xor(part[j], 32);
             const float ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
-            const int row = w0 + cb * 32 + n;
+            // the row's position again: from LDS on the sparse path (not held in a register since the fragment loads)
+            const int row = sparse ? spos[cb * 256 + tid] : w0 + cb * 32 + n;
             if (half == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
         }
     }
@@ -310,7 +385,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         plain_from = 0;
         plain_to = max(0, min(n_plain, n_it));
     } else {
-        const int n_masked = (w0 + 63 - x_begin + BX - 1) / BX;
+        const int n_masked = (min(p_wave_hi, L) - x_begin + BX - 1) / BX;
         plain_from = max(0, min(n_masked, n_it));
         plain_to = n_it;
     }
@@ -341,7 +416,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         if (it + 1 < n_it) load_tile(x0 + BX, nxt);
         // wave-uniform: a tile that lies entirely outside the causal region is not computed at all
         const bool mask = !(it >= plain_from && it < plain_to);
-        const bool skip = mask && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < w0));
+        const bool skip = mask && ((PASS == 1) ? (x0 > w0 + 63) : (x0 + BX - 1 < p_wave_lo));
 
         // End of the tile's LDS reads: wait for the next tile's loads, meet the other waves, and fetch the next
         // tile's first fragments - before the epilogue of this tile's second block, which hides their latency.
@@ -385,11 +460,12 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             auto epilogue = [&](int rb) {
                 const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
                 if (mask) {      // a scalar branch; both sides leave the prefetched fragments alone
-                    if (PASS == 1) lse_pair_epilogue<true>(Xc, Yc, scale2, xb, sA, sB, m, l);
-                    else colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, sA, sB, run);
+                    if (PASS == 1) lse_pair_epilogue<true>(Xc, Yc, scale2, xb, w0 + n, w0 + 32 + n, m, l);
+                    else if (sparse) colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, spos[tid], spos[256 + tid], run);
+                    else colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, w0 + n, w0 + 32 + n, run);
                 } else {
-                    if (PASS == 1) lse_pair_epilogue<false>(Xc, Yc, scale2, xb, sA, sB, m, l);
-                    else colsum_pair_epilogue<false>(Xc, Yc, scale2, xb, sA, sB, run);
+                    if (PASS == 1) lse_pair_epilogue<false>(Xc, Yc, scale2, xb, 0, 0, m, l);
+                    else colsum_pair_epilogue<false>(Xc, Yc, scale2, xb, 0, 0, run);
                 }
             };
             if (PASS == 1) {
@@ -449,17 +525,51 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
 // Folds the chunks of every strip, in chunk order: pass 1 -> lse2[h, i] = log2 sum_j 2^(c q_i.k_j) per query
 // head; pass 2 -> scores[h, j] = A_s[j] per key head, the partials of its `group` query heads added in head
-// order (group = 1: one query head per key head).  One thread per (head, row).
+// order (group = 1: one query head per key head).  One thread per (head, row).  With key lists (pass 2 over the
+// competing keys only) row r of strip t is the list's entry t * 256 + r and its score goes to that key's
+// position; the workgroups nS .. 2 nS - 1 of the grid then write the inverse norms of the PROTECTED keys, which
+// pass 2 no longer holds (summed in the order of the stand-alone norm kernel, so all three give the same bits).
 template <int PASS>
 __global__ void __launch_bounds__(256)
 k_score_combine(int group, int L, int R0, int C, const float* __restrict__ part_a, const float* __restrict__ part_b,
-                float* __restrict__ out)
+                float* __restrict__ out, const int32_t* __restrict__ lists, const bf16_t* __restrict__ k,
+                float* __restrict__ rnorm, int nS)
 {
-    const int h = blockIdx.y, tile = blockIdx.x, r = threadIdx.x;
-    const int row = tile * BS + r;
-    if (row >= L) return;
-    const int CT = C * BX, nS = gridDim.x, G = (L + CT - 1) / CT;
-    const int g0 = first_chunk(PASS, tile, CT, R0), nc = strip_chunks(PASS, tile, L, CT, R0);
+    const int h = blockIdx.y, r = threadIdx.x;
+    int tile = blockIdx.x;
+    if (PASS == 2 && lists != nullptr && tile >= nS) {
+        // inverse norms of the protected keys: eight lanes per key, lane p summing the dims 8p .. 8p+7 and
+        // 64+8p .. 64+8p+7 in order, then a pairwise tree over the lanes - the order of the stand-alone norm kernel
+        if (rnorm == nullptr) return;
+        const int NP = lists[1], sub = r & 7;
+        for (int idx = (tile - nS) * 32 + (r >> 3); idx < NP; idx += 32 * nS) {     // uniform per group of eight lanes
+            const int pos = lists[LIST_HEAD + L + idx];
+            const bf16_t* row = k + ((size_t)h * L + pos) * SD;
+            float ss = 0.f;
+#pragma unroll
+            for (int rep = 0; rep < 2; ++rep) {
+                float v[8];
+                load8(row + sub * 8 + rep * 64, v);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) ss = fmaf(v[i], v[i], ss);
+            }
+            ss += __shfl_xor(ss, 1);
+            ss += __shfl_xor(ss, 2);
+            ss += __shfl_xor(ss, 4);
+            if (sub == 0) rnorm[(size_t)h * L + pos] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
+        }
+        return;
+    }
+    const bool sparse = PASS == 2 && lists != nullptr;
+    int row = tile * BS + r;
+    if (row >= (sparse ? lists[0] : L)) return;
+    const int CT = C * BX, G = (L + CT - 1) / CT;
+    int g0 = first_chunk(PASS, tile, CT, R0), nc = strip_chunks(PASS, tile, L, CT, R0);
+    if (sparse) {
+        g0 = max((lists[LIST_HEAD + tile * BS] / BX) * BX, (R0 / BX) * BX) / CT;    // as in k_score_mfma
+        nc = G - g0;
+        row = lists[LIST_HEAD + row];
+    }
     if (nc == 0) return;     // pass 1 under a window: a strip with no row that counts (its values are never read)
     const int t_base = (PASS == 1) ? R0 / BS : 0, nSp = nS - t_base;   // as in k_score_mfma
     const size_t stride = (size_t)nSp * BS;     // from one chunk of a strip to the next
@@ -523,8 +633,11 @@ size_t scores_mfma_scratch_floats(int H, int L)
     return (size_t)2 * H * G * nS * lookm::BS;
 }
 
+// mask / M / lists: when given (the caller does not want the scores of the protected keys), pass 2 runs over the
+// competing keys only; lists: device, 2 * L + LIST_HEAD ints
 int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L, int d, int R0, float* lse,
-                       const float* lse_in, float* scores, float* rnorm, float* scratch, hipStream_t st)
+                       const float* lse_in, float* scores, float* rnorm, float* scratch, const uint8_t* mask, int M,
+                       int32_t* lists, hipStream_t st)
 {
     if (d != lookm::SD) return LOOKM_ERR_UNSUPPORTED;
     const LaunchCheck check;
@@ -548,19 +661,31 @@ int launch_scores_mfma(const void* q, const void* k, int H, int kv_heads, int L,
     const float scale2 = lookm::kLog2e / sqrtf((float)d);
     const lookm::bf16_t* qq = (const lookm::bf16_t*)q;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
+    const bool sparse = mask != nullptr && lists != nullptr;
     if (!lse_in) {
-        hipLaunchKernelGGL(lookm::k_score_mfma<1>, dim3(score_grid(H, U1)), dim3(256), 0, st, qq, kk, H, group, L, R0,
-                           scale2, C1, U1, lse, 1.0f, part_a, part_b, (float*)nullptr);
+        // with a mask the launch has one workgroup more: it builds the key lists while the others compute
+        hipLaunchKernelGGL((lookm::k_score_mfma<1, false>), dim3(score_grid(H, U1) + (sparse ? 1u : 0u)), dim3(256), 0, st, qq, kk, H,
+                           group, L, R0, scale2, C1, U1, lse, 1.0f, part_a, part_b, (float*)nullptr,
+                           sparse ? mask : (const uint8_t*)nullptr, M, lists);
         mark(LOOKM_K_SCORE_LSE);
-        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, 1, L, R0, C1, part_a, part_b, lse);
+        hipLaunchKernelGGL(lookm::k_score_combine<1>, dim3(nS, H), dim3(256), 0, st, 1, L, R0, C1, part_a, part_b, lse,
+                           (const int32_t*)nullptr, (const lookm::bf16_t*)nullptr, (float*)nullptr, nS);
         mark(LOOKM_K_SCORE_LSE_FOLD);
+    } else if (sparse) {
+        hipLaunchKernelGGL(lookm::k_score_lists, dim3(1), dim3(256), 0, st, mask, L, M, lists);
     }
     // a caller-supplied row log-sum-exp is natural-log: one factor log2(e) brings it to the kernels' base
-    hipLaunchKernelGGL(lookm::k_score_mfma<2>, dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, group, L, R0, scale2,
-                       C, U2, lse_in ? lse_in : lse, (lse_in ? lookm::kLog2e : 1.0f) / scale2, part_a, part_b, rnorm);
+    if (sparse)
+        hipLaunchKernelGGL((lookm::k_score_mfma<2, true>), dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, group, L,
+                           R0, scale2, C, U2, lse_in ? lse_in : lse, (lse_in ? lookm::kLog2e : 1.0f) / scale2, part_a,
+                           part_b, rnorm, (const uint8_t*)nullptr, M, lists);
+    else
+        hipLaunchKernelGGL((lookm::k_score_mfma<2, false>), dim3(score_grid(H, U2)), dim3(256), 0, st, qq, kk, H, group, L,
+                           R0, scale2, C, U2, lse_in ? lse_in : lse, (lse_in ? lookm::kLog2e : 1.0f) / scale2, part_a,
+                           part_b, rnorm, (const uint8_t*)nullptr, M, (int32_t*)nullptr);
     mark(LOOKM_K_SCORE_COLSUM);
-    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(nS, kv_heads), dim3(256), 0, st, group, L, R0, C, part_a, part_b,
-                       scores);
+    hipLaunchKernelGGL(lookm::k_score_combine<2>, dim3(sparse ? 2 * nS : nS, kv_heads), dim3(256), 0, st, group, L, R0, C,
+                       part_a, part_b, scores, sparse ? (const int32_t*)lists : (const int32_t*)nullptr, kk, rnorm, nS);
     mark(LOOKM_K_SCORE_COLSUM_FOLD);
     return check.status();
 }

@@ -133,8 +133,14 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None, M=Non
     qg, kg, vg, mg = to_gpu(q, k, v, mask)
     H, L, d = q.shape
     ws = lookm.alloc_workspace(H, L, d, B, lookm._dt(qg), qg.device)
+    # first without the scores: the second score pass may then skip the keys that do not compete in the selection
+    # (matrix-core path, default rule); the cache must come out bit for bit as when every score is computed
+    lean = lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, want_scores=False, rule=rule, workspace=ws)
+    lean = (lean.kept_idx.clone(), lean.k_out.clone(), lean.v_out.clone())
     res = lookm.lookm_compress(qg, kg, vg, mg, B, M, mode, want_scores=True, rule=rule, workspace=ws)
     torch.cuda.synchronize()
+    assert torch.equal(lean[0], res.kept_idx) and torch.equal(lean[1], res.k_out) and torch.equal(lean[2], res.v_out), \
+        "the call without scores_out gives a different cache"
     st = check_outputs(q, k, v, mask, B, M, mode, rule, res, ws, oracle_heads)
     st = dict(workload=label or w.name, layer=layer, mode=mode, rule=rule, H=H, L=L, B=B, M=M, **st)
     return record(**st)

@@ -122,6 +122,46 @@ def test_stack_jobs_at_full_size_through_one_batch_call():
     assert torch.equal(alone.v_out, outs[(w.name, 17)].v_out)
 
 
+@pytest.mark.parametrize("case", ["plain", "window", "row_lse", "grouped", "no_image", "no_text", "window_covers_images"])
+def test_second_score_pass_over_the_competing_keys_only(case):
+    """Without scores_out (and under the default rule) the second score pass runs over the image tokens before the
+    recent window only, through a list of their positions.  Everything a key's score is summed from is unchanged, so
+    the cache must be bit for bit the one of the call that computes every score."""
+    dev = torch.device("cuda:0")
+    w = W.LLAVA7B
+    q, k, v, mask = W.generate(w, heads=[0, 3, 5, 6, 9, 12, 20, 31, 2])
+    B, M = w.budget(), w.M
+    kw = {}
+    if case == "window":
+        kw["score_window"] = 700
+    elif case == "row_lse":
+        kw["row_lse"] = torch.from_numpy(oracle.row_lse(q, k)).float().to(dev)
+    elif case == "grouped":
+        q, k, v = q[:8], k[[0, 4]].contiguous(), v[[0, 4]].contiguous()
+    elif case == "no_image":                       # nothing competes: every key is text, everything is conserved
+        mask = torch.zeros_like(mask)
+        B = w.L
+    elif case == "no_text":                        # every key before the window competes
+        mask = torch.ones_like(mask)
+        B = 700
+    elif case == "window_covers_images":           # the window holds every image token: nothing competes either
+        M = w.L - 96
+        B = w.L - 40                               # (the default rule then needs B >= text + window = L: refused)
+    args = [t.to(dev) for t in (q, k, v, mask)]
+    if case == "window_covers_images":
+        for want in (True, False):
+            with pytest.raises(lookm.LookmError) as e:
+                lookm.lookm_compress(*args, B, M, "pivotal", want_scores=want)
+            assert e.value.code == lookm.ERR_BUDGET_BELOW_PROTECTED
+        B = w.L
+    full = lookm.lookm_compress(*args, B, M, "pivotal", want_scores=True, **kw)
+    lean = lookm.lookm_compress(*args, B, M, "pivotal", want_scores=False, **kw)
+    assert torch.equal(full.kept_idx, lean.kept_idx)
+    assert torch.equal(full.k_out, lean.k_out) and torch.equal(full.v_out, lean.v_out)
+    again = lookm.lookm_compress(*args, B, M, "pivotal", want_scores=False, **kw)
+    assert torch.equal(again.k_out, lean.k_out) and torch.equal(again.kept_idx, lean.kept_idx)
+
+
 def test_text_prior_off():
     w = W.LLAVA7B
     q, k, v, mask = W.generate(w, heads=[0, 1])
