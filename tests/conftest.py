@@ -55,11 +55,12 @@ def pytest_sessionfinish(session, exitstatus):
     width = [max(len(c), *(len(r[i]) for r in rows)) for i, c in enumerate(cols)]
     with open(path, "w") as f:
         f.write("GPU path against the CPU oracle, one line per checked call (tests/parity.py):\n"
-                "heads = heads run on the GPU, all of them checked stage-exact (selection on the kernel's own scores, merge on\n"
-                "the call's own matching); heads_oracle = heads also compared with the fp64 oracle end to end;\n"
-                "kept_diff_heads = of those, heads whose kept set differs from the oracle's; min_margin = smallest relative gap\n"
-                "between the last conserved and the first evicted competing score (fp64 oracle); nearest_tie_rows = evicted keys\n"
-                "matched to another slot than the oracle's, of rows_matched; score_relerr, sim_abserr, merge_abserr = largest\n"
+                "heads = heads run on the GPU, all of them checked stage by stage (selection on the kernel's own scores, the\n"
+                "matching against the fp64 oracle's on the call's own lists, merge on the call's own matching); heads_oracle =\n"
+                "heads whose scores and kept sets are also compared with the fp64 oracle end to end; kept_diff_heads = of\n"
+                "those, heads whose kept set differs from the oracle's; min_margin = smallest relative gap between the last\n"
+                "conserved and the first evicted competing score (fp64 oracle); nearest_tie_rows = evicted keys matched to\n"
+                "another slot than the oracle's, of rows_matched (all heads); score_relerr, sim_abserr, merge_abserr = largest\n"
                 "errors seen (scores relative, cosines absolute, merged rows absolute against unrounded fp64).\n"
                 f"pytest exit status {int(exitstatus)}\n\n")
         f.write("  ".join(c.ljust(width[i]) for i, c in enumerate(cols)) + "\n")
