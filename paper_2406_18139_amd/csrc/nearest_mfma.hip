@@ -18,12 +18,13 @@
 // Exact decisions.  The matrix-core value of y differs from the true one by well under one unit (fp32
 // accumulation of exact products, one fp32 inverse norm, one product: a few ulp), so the true maximum can only
 // be a key whose truncated value lies within NEAR_UNITS units of the best one.  Besides the best key, a lane
-// therefore keeps (i) the largest runner-up INSIDE a 32x32 block it has seen and (ii) a bit mask of the blocks
-// whose best value came within NEAR_UNITS units of its running best (cleared whenever the best jumps by more
-// than that, so that at the end it marks exactly the blocks that can still hold a contender).  k_nearest_fold
-// takes the matrix-core choice where the winner's block is the only marked one and its runner-up inside the
-// block is farther away; every other evicted key (one in six hundred at the headline shape) is decided again
-// exactly: the slots of the marked blocks are evaluated in binary64 with a fixed arithmetic contract -
+// therefore keeps (i) the largest runner-up INSIDE a 32x32 block it has seen and (ii) per block class (block
+// number modulo the number of classes: 32, 16 or 8) a count of the blocks whose best value came within NEAR_UNITS units of its running best (all
+// cleared whenever the best jumps by more than that, so that at the end the counters cover every block that can
+// still hold a contender; counts rather than bits, because two such blocks may fall into one class).
+// k_nearest_fold takes the matrix-core choice where the winner's block is the only one counted and its runner-up
+// inside the block is farther away; every other evicted key (one in six hundred at the headline shape) is decided again
+// exactly: the slots of every block of the classes counted are evaluated in binary64 with a fixed arithmetic contract -
 // sequential sums over k = 0..d-1 of products that are exact in binary64, binary64 square roots, one product,
 // one division, first maximum in slot order - which is a definition, not an approximation, so any
 // implementation of the same contract takes the same decision.
@@ -50,15 +51,30 @@ constexpr int NEAR_UNITS = 2;   // a runner-up within this many units of the bes
 //   key   (truncated value of the best conserved key) << 4 | how many units the best runner-up inside a block of the
 //         winning lane lies below it (15 = fifteen or more)
 //   slot  the best key's slot
-//   marks bits 0-15 and 16-31: per lane of the pair (first: slots 0-3 of every eight, second: slots 4-7), bit b set
-//         if the blocks b, b + 16, ... of the chunk can hold a key within NEAR_UNITS units of the chunk's best
-//         value; zero for a lane whose own best value is farther away than that
-struct NearestPartial {
+//   marks per lane of the pair (first: slots 0-3 of every eight, second: slots 4-7) a word of 32 / w counters of
+//         w bits: counter b = how many of the blocks b, b + 32 / w, ... of the chunk can hold a key within
+//         NEAR_UNITS units of the chunk's best value (a COUNT, so that two such blocks of one class are still seen
+//         as two); zero for a lane whose own best value is farther away than that.  w = 1, 2 or 4 is the
+//         narrowest width whose counters can count all blocks of a class (near_counter_bits): a chunk of up to
+//         32 blocks has a class per block.
+struct __attribute__((aligned(16))) NearestPartial {
     int32_t key;
     int32_t slot;
-    uint32_t marks;
+    uint32_t marks[2];
 };
-constexpr int NEAR_MASK_BITS = 16;
+constexpr int NEAR_MAX_BLOCKS = 120;       // per chunk: eight 4-bit counters count 15 blocks each
+constexpr int NEAR_MAX_CHUNKS = 9;         // LOOKM_MAX_L / 64 tiles in chunks of at most 60 tiles (120 blocks)
+
+// counter width for a chunk of nb blocks: 32 classes of 1 bit, 16 of 2 bits (up to 3 blocks each) or 8 of 4 bits
+__host__ __device__ inline int near_counter_bits(int nb) { return nb <= 32 ? 1 : nb <= 48 ? 2 : 4; }
+
+// sum of the counters of a mark word
+__device__ __forceinline__ int near_count(uint32_t m, int bits)
+{
+    if (bits == 1) return __popc(m);
+    if (bits == 2) m = (m & 0x33333333u) + ((m >> 2) & 0x33333333u);    // pairs of counters: at most 6 per nibble
+    return (int)((((m & 0x0f0f0f0fu) + ((m >> 4) & 0x0f0f0f0fu)) * 0x01010101u) >> 24);
+}
 
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
 __device__ __forceinline__ int imed3(int a, int b, int c) { return max(min(a, b), min(max(a, b), c)); }
@@ -83,7 +99,7 @@ __device__ __forceinline__ void top2_of_16(const int (&u)[16], int& first, int& 
 __global__ void __launch_bounds__(256, 3)
 k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
                const int32_t* __restrict__ evicted, int H, int L, int B, int Le, int n_strips, int n_chunks, int CT,
-               NearestPartial* __restrict__ part)
+               int cbits, NearestPartial* __restrict__ part)
 {
     // Two tiles as separate arrays, and a tile loop unrolled by two with the buffer known at compile time: the
     // compiler then sees that a fragment read of one array cannot alias the loads in flight to the other and
@@ -182,7 +198,8 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     int bkey[2] = {KEY_MIN | 15, KEY_MIN | 15};   // best key (low 4 bits: 15 - entry number)
     int bsec[2] = {KEY_MIN, KEY_MIN};             // largest runner-up inside one block
     int bxb[2] = {0, 0};                          // slot of entry 0 of the block the best key came from
-    uint32_t bnear[2] = {0u, 0u};                 // blocks (mod 16) that can still hold a contender
+    uint32_t bnear[2] = {0u, 0u};                 // per block class, how many blocks can still hold a contender
+    const int cls_mask = 32 / cbits - 1;          // classes are block numbers modulo their count
 
     LOOKM_LOAD_INDEX(x_begin);           // in flight together with the evicted positions
 
@@ -231,7 +248,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], acc[1], 0, 0, 0);
             }
             const int xb = x0 + rb * 32 + 4 * half;   // slot of entry r: xb + 8*(r/4) + r%4
-            const uint32_t blk_bit = 1u << ((2 * it + rb) & (NEAR_MASK_BITS - 1));
+            const uint32_t blk_one = 1u << (cbits * ((2 * it + rb) & cls_mask));   // one in this block's counter
             const float* rp = &cur_r[rb * 32 + 4 * half];
 #pragma unroll
             for (int cb = 0; cb < 2; ++cb) {
@@ -255,7 +272,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 // the running best (from either side) stays a candidate
                 const int ahead = __builtin_elementwise_sub_sat(bm, bkey[cb]);   // saturating: the first block's lead is huge
                 bnear[cb] = (ahead > NEAR_KEY) ? 0u : bnear[cb];
-                bnear[cb] |= (ahead >= -NEAR_KEY) ? blk_bit : 0u;
+                bnear[cb] += (ahead >= -NEAR_KEY) ? blk_one : 0u;   // cannot overflow: see near_counter_bits
                 bsec[cb] = max(bsec[cb], bs2);
                 bkey[cb] = better ? bm : bkey[cb];
                 bxb[cb] = better ? xb : bxb[cb];
@@ -292,7 +309,8 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             NearestPartial p;
             p.key = (int)(((uint32_t)hi << 4) | (uint32_t)min(hi - sec, 15));   // sec <= hi
             p.slot = slot;
-            p.marks = mine | (theirs << 16);
+            p.marks[0] = mine;
+            p.marks[1] = theirs;
             out[wave * 64 + cb * 32 + n] = p;
         }
     }
@@ -361,6 +379,7 @@ constexpr int NF_LDS_CHUNKS = 4;  // chunks whose block masks the fold keeps in 
 // whose best value is not positive (integer order of the bits is not float order there) takes every slot.
 // (few registers and little LDS on purpose: all workgroups of the headline shape are resident at once, so the
 // kernel takes as long as its slowest workgroup, not twice that)
+template <int cbits>   // counter width of the mark words (near_counter_bits of the chunk length)
 __global__ void __launch_bounds__(NF_THREADS, 6)
 k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, const int32_t* __restrict__ kept,
                const int32_t* __restrict__ evicted, int L, int B, int Le, int n_strips, int n_chunks, int CT,
@@ -370,7 +389,7 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     __shared__ int item_pos_c[NF_ITEMS];      // position of the item's conserved key
     __shared__ int item_slot[NF_ITEMS];
     __shared__ double item_s[NF_ITEMS];
-    __shared__ uint32_t near_m[NF_LDS_CHUNKS][NF_THREADS];   // marked blocks per key and chunk (both lanes' masks); 0: chunk out of reach
+    __shared__ uint2 near_m[NF_LDS_CHUNKS][NF_THREADS];      // block counters per key and chunk (both lanes'); 0: chunk out of reach
     __shared__ int n_items;
     const int h = blockIdx.y, tid = threadIdx.x;
     k += (size_t)h * L * ND;
@@ -387,26 +406,26 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     if (ev < Le) {
         pos_e = evicted[ev];
         mine = part + ((size_t)h * n_chunks * n_strips + ev / NBS) * NBS + ev % NBS;
-        int key[8], bs = 0x7fffffff, bd = 15, marks[8];
+        int key[NEAR_MAX_CHUNKS], bs = 0x7fffffff, bd = 15, marks[NEAR_MAX_CHUNKS];
         bk = (int)0x80000000;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < NEAR_MAX_CHUNKS; ++c) {
             key[c] = (int)0x80000000;
             marks[c] = 0;
             if (c < n_chunks) {
                 const NearestPartial p = mine[(size_t)c * n_strips * NBS];
                 key[c] = p.key >> 4;
-                marks[c] = __popc(p.marks);
-                if (c < NF_LDS_CHUNKS) near_m[c][tid] = p.marks;
+                marks[c] = near_count(p.marks[0], cbits) + near_count(p.marks[1], cbits);
+                if (c < NF_LDS_CHUNKS) near_m[c][tid] = make_uint2(p.marks[0], p.marks[1]);
                 if (key[c] > bk || (key[c] == bk && p.slot < bs)) { bk = key[c]; bs = p.slot; bd = p.key & 15; }
             }
         }
         int marked = 0;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < NEAR_MAX_CHUNKS; ++c) {
             const bool reach = key[c] >= bk - NEAR_UNITS;          // chunks within reach only
             marked += reach ? marks[c] : 0;
-            if (c < NF_LDS_CHUNKS && c < n_chunks && !reach) near_m[c][tid] = 0u;
+            if (c < NF_LDS_CHUNKS && c < n_chunks && !reach) near_m[c][tid] = make_uint2(0u, 0u);
         }
         // bk <= 0: the best value is zero or negative; every slot is a candidate then
         pending = bk <= 0 || bd <= NEAR_UNITS || marked > 1;
@@ -418,21 +437,25 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     }
     if (!__syncthreads_or(pending)) return;
 
-    // The marked blocks of chunk c for this thread's key (zero when the chunk is out of reach).
+    // The block counters of chunk c for this thread's key (zero when the chunk is out of reach).
     auto chunk_marks = [&](int c, uint32_t (&m)[2]) {
-        uint32_t both;
-        if (c < NF_LDS_CHUNKS) both = near_m[c][tid];
-        else {                                                         // more chunks than LDS holds: read again
+        if (c < NF_LDS_CHUNKS) {
+            const uint2 both = near_m[c][tid];
+            m[0] = both.x;
+            m[1] = both.y;
+        } else {                                                       // more chunks than LDS holds: read again
             const NearestPartial p = mine[(size_t)c * n_strips * NBS];
-            both = ((p.key >> 4) >= bk - NEAR_UNITS) ? p.marks : 0u;
+            const bool reach = (p.key >> 4) >= bk - NEAR_UNITS;
+            m[0] = reach ? p.marks[0] : 0u;
+            m[1] = reach ? p.marks[1] : 0u;
         }
-        m[0] = both & 0xffffu;
-        m[1] = both >> 16;
     };
     // Walks through the candidate slots of this thread's key - the 16 slots of every marked block of every chunk
     // within reach, or every slot when the best value is not positive; slots past the end of the conserved list
-    // are reported as -1 (so that a block always yields 16 entries).  Bit b of a mask stands for the blocks b,
-    // b + 16, ... of the chunk.
+    // are reported as -1 (so that a block always yields 16 entries).  A non-zero counter b stands for the blocks b,
+    // b + n_cls, ... of the chunk, all of which are visited.
+    constexpr int n_cls = 32 / cbits, cls_shift = cbits >> 1;  // counter number = bit number >> cls_shift
+    constexpr uint32_t field = (1u << cbits) - 1u;
     auto for_each_candidate = [&](auto&& visit) {
         if (bk <= 0) {
             for (int s = 0; s < B; ++s) visit(s);
@@ -444,8 +467,10 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             const int lo = c * CT, hi = min(B, lo + CT);
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
-                for (uint32_t rest = m[half]; rest != 0u; rest &= rest - 1u) {
-                    for (int b = __ffs((int)rest) - 1; lo + 32 * b < hi; b += NEAR_MASK_BITS) {
+                for (uint32_t rest = m[half]; rest != 0u;) {
+                    const int cls = (__ffs((int)rest) - 1) >> cls_shift;
+                    rest &= ~(field << (cbits * cls));
+                    for (int b = cls; lo + 32 * b < hi; b += n_cls) {
                         for (int g = 0; g < 16; ++g) {
                             const int s = lo + 32 * b + 4 * half + 8 * (g >> 2) + (g & 3);
                             visit(s < hi ? s : -1);
@@ -465,9 +490,10 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 const int nb = (min(B, (c + 1) * CT) - c * CT + 31) / 32;      // blocks of this chunk
 #pragma unroll
                 for (int half = 0; half < 2; ++half)
-                    for (uint32_t rest = m[half]; rest != 0u; rest &= rest - 1u) {
-                        const int b = __ffs((int)rest) - 1;
-                        cnt += (b < nb) ? 16 * ((nb - b + NEAR_MASK_BITS - 1) / NEAR_MASK_BITS) : 0;
+                    for (uint32_t rest = m[half]; rest != 0u;) {
+                        const int cls = (__ffs((int)rest) - 1) >> cls_shift;
+                        rest &= ~(field << (cbits * cls));
+                        cnt += (cls < nb) ? 16 * ((nb - cls + n_cls - 1) / n_cls) : 0;
                     }
             }
     }
@@ -529,7 +555,8 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
 namespace lookm_host {
 
 // chunks of the conserved axis: the count (at most 8, at least 4 tiles each) whose workgroup total fills
-// the resident slots (256 CUs x 3) most evenly
+// the resident slots (256 CUs x 3) most evenly - more if a chunk would otherwise hold more blocks of one class
+// than a mark counter can count
 static int nearest_chunks(int H, int Le, int B)
 {
     const int strips = (Le + lookm::NBS - 1) / lookm::NBS, tiles = (B + lookm::NBX - 1) / lookm::NBX;
@@ -540,6 +567,7 @@ static int nearest_chunks(int H, int Le, int B)
         const double eff = (double)units / (double)(((units + 767) / 768) * 768);
         if (eff > best_eff + 0.02) { best_eff = eff; best = c; }
     }
+    while (2 * ((tiles + best - 1) / best) > lookm::NEAR_MAX_BLOCKS) ++best;   // two blocks per tile
     return best;
 }
 
@@ -548,7 +576,7 @@ size_t nearest_mfma_scratch_bytes(int H, int L, int B)
     const int Le = L - B;
     if (Le <= 0 || B <= 0) return 0;
     const int strips = (Le + lookm::NBS - 1) / lookm::NBS;
-    return (size_t)H * 8 * strips * lookm::NBS * sizeof(lookm::NearestPartial);
+    return (size_t)H * nearest_chunks(H, Le, B) * strips * lookm::NBS * sizeof(lookm::NearestPartial);
 }
 
 int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evicted, int H, int L, int budget,
@@ -560,18 +588,25 @@ int launch_nearest_mfma(const void* k, const int32_t* kept, const int32_t* evict
     const int nc = nearest_chunks(H, Le, B);
     const int CT = ((tiles + nc - 1) / nc) * lookm::NBX;        // conserved slots per chunk
     const int n_chunks = (B + CT - 1) / CT;
+    if (n_chunks > lookm::NEAR_MAX_CHUNKS) return LOOKM_ERR_UNSUPPORTED;   // cannot happen for L <= LOOKM_MAX_L
     const int U = strips * n_chunks;
+    const int cbits = lookm::near_counter_bits(CT / 32);        // blocks of a full chunk
     unsigned grid;
     if (H >= 8) grid = 8u * (unsigned)((H + 7) / 8) * (unsigned)U;
     else { const int xph = 8 / H; grid = 8u * (unsigned)((U + xph - 1) / xph); }
     lookm::NearestPartial* part = (lookm::NearestPartial*)scratch;
     const lookm::bf16_t* kk = (const lookm::bf16_t*)k;
     hipLaunchKernelGGL(lookm::k_nearest_mfma, dim3(grid), dim3(256), 0, st, kk, rnorm, kept, evicted, H, L, B, Le, strips,
-                       n_chunks, CT, part);
+                       n_chunks, CT, cbits, part);
     mark(LOOKM_K_NEAREST);
-    hipLaunchKernelGGL(lookm::k_nearest_fold, dim3((Le + lookm::NF_THREADS - 1) / lookm::NF_THREADS, H),
-                       dim3(lookm::NF_THREADS), 0, st, kk, rnorm, kept, evicted, L, B, Le, strips, n_chunks, CT, part,
-                       assign, sim);
+    const dim3 fold_grid((Le + lookm::NF_THREADS - 1) / lookm::NF_THREADS, H);
+#define LOOKM_FOLD(W)                                                                                                  \
+    hipLaunchKernelGGL(lookm::k_nearest_fold<W>, fold_grid, dim3(lookm::NF_THREADS), 0, st, kk, rnorm, kept, evicted, \
+                       L, B, Le, strips, n_chunks, CT, part, assign, sim)
+    if (cbits == 1) LOOKM_FOLD(1);
+    else if (cbits == 2) LOOKM_FOLD(2);
+    else LOOKM_FOLD(4);
+#undef LOOKM_FOLD
     mark(LOOKM_K_NEAREST_FOLD);
     return check.status();
 }
