@@ -294,6 +294,24 @@ def test_nearest_exact_ties_and_zero_keys():
     assert np.array_equal(a, ra)
 
 
+def test_nearest_when_every_cosine_is_negative():
+    """Evicted keys that point away from every conserved key: the best cosine is negative, where the integer order
+    of float bits is the reverse of their value order - those rows are decided by the exact pass over all slots."""
+    L, d, B = 700, 128, 300
+    g = torch.Generator().manual_seed(5)
+    v = torch.randn(d, generator=g)
+    k = torch.empty(1, L, d)
+    kept, ev = split(L, B, 6)
+    k[0, kept] = v + 0.3 * torch.randn(B, d, generator=g)
+    k[0, ev] = -v + 0.3 * torch.randn(L - B, d, generator=g)
+    k = k.to(torch.bfloat16)
+    a, s = lookm.lookm_nearest(k.cuda(), torch.from_numpy(kept)[None].cuda(), torch.from_numpy(ev)[None].cuda())
+    ra, rs = oracle.nearest(k[0].float().numpy(), kept, ev)
+    assert rs.max() < 0
+    assert np.array_equal(a.cpu().numpy()[0], ra)
+    np.testing.assert_allclose(s.cpu().numpy()[0], rs, rtol=0, atol=parity.SIM_ATOL)
+
+
 @pytest.mark.parametrize("H,Le", [(1, 512), (16, 12288), (3, 30000)])
 def test_nearest_near_ties_between_far_apart_blocks(H, Le):
     """Pairs (and triples) of conserved keys whose cosines to an evicted key differ by a few 1e-7 - less than the
@@ -328,6 +346,46 @@ def test_nearest_near_ties_between_far_apart_blocks(H, Le):
     twins = int(np.sum(ra >= n_src))
     print(f"near ties: {len(rows)} rows checked, {twins} matched to a twin, {int(np.sum(a[0][rows] != ra))} differ")
     assert len(rows) // 8 < twins < len(rows)                         # both members of a pair win somewhere
+    assert np.array_equal(a[0][rows], ra)
+    np.testing.assert_allclose(s[0][rows], rs, rtol=0, atol=parity.SIM_ATOL)
+
+
+@pytest.mark.parametrize("H,B,Le", [(16, 2048, 12288), (32, 3072, 9216), (2, 1000, 3000)])
+def test_nearest_near_ties_scattered_over_the_conserved_axis(H, B, Le):
+    """Near-tied conserved keys at random slots (any lane, any entry of a block, any chunk; some in threes), with
+    cosine gaps from 3e-8 to 4e-6 - from far below to just above what the matrix-core values resolve - and an
+    evicted key for each that prefers one or the other by the sign of one small component.  Chunks of 64, 48 and 8
+    blocks: every counter width of the block marks.  The matching must be the binary64 one on every checked row."""
+    d = 128
+    rng = np.random.default_rng(B + Le)
+    g = torch.Generator().manual_seed(B)
+    kept_k = torch.randn(B, d, generator=g)
+    kept_k[:, 5] = 0
+    n_src = B // 5
+    slots = rng.permutation(B)
+    src_slot, twin_slot, third_slot = slots[:n_src], slots[n_src:2 * n_src], slots[2 * n_src:3 * n_src]
+    p_exp = rng.integers(6, 10, n_src)
+    for i in range(n_src):
+        kept_k[twin_slot[i]] = kept_k[src_slot[i]]
+        kept_k[twin_slot[i], 5] = 2.0 ** -int(p_exp[i])
+        if i % 3 == 0:
+            kept_k[third_slot[i]] = kept_k[src_slot[i]]
+            kept_k[third_slot[i], 5] = -(2.0 ** -int(p_exp[i]))
+    which = torch.from_numpy(rng.integers(0, n_src, Le))
+    ev_k = kept_k[torch.from_numpy(src_slot)[which]] + 0.05 * torch.randn(Le, d, generator=g)
+    q_exp = torch.from_numpy(rng.integers(5, 10, Le)).float()
+    sign = torch.from_numpy(rng.choice([-1.0, 1.0], Le)).float()
+    ev_k[:, 5] = sign * 2.0 ** -q_exp
+    k1 = torch.cat([kept_k, ev_k]).to(torch.bfloat16)
+    k = k1[None].expand(H, -1, -1).contiguous()
+    kept = np.tile(np.arange(B, dtype=np.int32), (H, 1))
+    ev = np.tile(np.arange(B, B + Le, dtype=np.int32), (H, 1))
+    a, s = lookm.lookm_nearest(k.cuda(), torch.from_numpy(kept).cuda(), torch.from_numpy(ev).cuda())
+    a, s = a.cpu().numpy(), s.cpu().numpy()
+    assert all(np.array_equal(a[h], a[0]) and np.array_equal(s[h], s[0]) for h in range(H))
+    rows = np.arange(0, Le, max(1, Le // 1500))
+    ra, rs = oracle.nearest(k1.float().numpy(), kept[0], ev[0][rows])
+    print(f"scattered near ties: {len(rows)} rows checked, {int(np.sum(a[0][rows] != ra))} differ")
     assert np.array_equal(a[0][rows], ra)
     np.testing.assert_allclose(s[0][rows], rs, rtol=0, atol=parity.SIM_ATOL)
 
