@@ -202,8 +202,9 @@ def check_outputs(q, k, v, mask, B, M, mode, rule, res, ws, oracle_heads=None):
             stats["merge_abserr"] = max(stats["merge_abserr"],
                                         check_merge(x[h], kept_g[h], ev_ws[h], assign_g[h], sim_g[h], mode, o[h], q.dtype))
     # end to end against the fp64 oracle, sampled heads
-    if oh:
-        ref_scores = oracle.scores(q[oh], k[oh])
+    if oh:                                 # one head per thread: the C oracle runs outside the interpreter lock
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as pool:
+            ref_scores = np.stack(list(pool.map(lambda h: oracle.scores(q[h], k[h]), oh)))
     for n, h in enumerate(oh):
         stats["score_relerr"] = max(stats["score_relerr"], check_scores(scores_g[h].astype(np.float64), ref_scores[n]))
         ref_kept, _ = oracle.select(ref_scores[n], mask_np, B, M, rule)

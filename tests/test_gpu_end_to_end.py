@@ -39,14 +39,15 @@ def test_llava7b_shaped_layer(mode):
 @pytest.mark.parametrize("rho", [0.1, 0.2, 0.4])
 def test_llava13b_shaped_layer(rho):
     w = W.llava13b(rho)
-    st = parity.run_and_check(w, "weighted", oracle_heads=[0, 7, 13, 20, 26, 33, 39])
+    st = parity.run_and_check(w, "weighted")          # all 40 heads against the fp64 oracle
     print(w.name, st)
     assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
 
 def test_long_multi_image_layer_full_size():
-    # the headline shape: GPU on all 32 heads, every one checked stage-exact; the fp64 oracle (9 s per head) on six
-    st = parity.run_and_check(W.LONG, "pivotal", oracle_heads=[0, 5, 11, 17, 24, 31])
+    # the headline shape: all 32 heads on the GPU, every one of them against the fp64 oracle end to end (9 s of CPU
+    # per head, one head per host thread)
+    st = parity.run_and_check(W.LONG, "pivotal")
     print("long", st)
     assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
@@ -69,15 +70,15 @@ def test_long_layer_without_text_prior():
 def test_stack_prompts_two_layers_each():
     for w in W.stack_prompts()[:2]:
         for layer in (0, 31):
-            st = parity.run_and_check(w, "weighted", heads=[0, 1, 2, 3], layer=layer, oracle_heads=[1])
+            st = parity.run_and_check(w, "weighted", heads=[0, 1, 2, 3], layer=layer)
             print(w.name, layer, st)
             assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
 
 def test_stack_long_prompts_one_layer_each():
-    # the 9K and 12K prompts of the stack: GPU on four heads, oracle on two of them
+    # the 9K and 12K prompts of the stack: four heads each
     for w, layer in zip(W.stack_prompts()[2:], (15, 7)):
-        st = parity.run_and_check(w, "weighted", heads=[4, 11, 18, 25], layer=layer, oracle_heads=[0, 3])
+        st = parity.run_and_check(w, "weighted", heads=[4, 11, 18, 25], layer=layer)
         print(w.name, layer, st)
         assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
@@ -85,8 +86,8 @@ def test_stack_long_prompts_one_layer_each():
 def test_stack_jobs_at_full_size_through_one_batch_call():
     """The 32-layer x 4-prompt stack at its real shape: 32-head jobs of three of its ragged prompts (4K, 6K and 12K
     tokens), two layers each, built from the host generator and issued through ONE two-stream batch call in the order
-    a prefill produces them, the layers of a prompt sharing its workspace.  Every head of every job is checked
-    stage-exact, sampled heads against the fp64 oracle."""
+    a prefill produces them, the layers of a prompt sharing its workspace.  Every head of every job is checked stage
+    by stage and, for the scores and the conserved sets, against the fp64 oracle end to end."""
     dev = torch.device("cuda:0")
     aux = torch.cuda.Stream()
     prompts = [W.stack_prompts()[p] for p in (0, 1, 3)]
@@ -102,7 +103,6 @@ def test_stack_jobs_at_full_size_through_one_batch_call():
             jobs.append(lookm.make_job(*gpu[key], w.budget(), w.M, "weighted", outs[key], wss[w.name]))
     lookm.lookm_compress_batch(jobs, aux_stream=aux)
     torch.cuda.synchronize()
-    sample = {prompts[0].name: [2, 30], prompts[1].name: [9, 16], prompts[2].name: [5, 27]}
     for layer in layers:
         for w in prompts:
             key = (w.name, layer)
@@ -110,8 +110,7 @@ def test_stack_jobs_at_full_size_through_one_batch_call():
             q, k, v, mask = host[key]
             # the workspace holds the intermediate results of the prompt's LAST layer only
             ws = wss[w.name] if layer == layers[-1] else None
-            st = parity.check_outputs(q, k, v, mask, w.budget(), w.M, "weighted", "protect_text", outs[key], ws,
-                                      oracle_heads=sample[w.name])
+            st = parity.check_outputs(q, k, v, mask, w.budget(), w.M, "weighted", "protect_text", outs[key], ws)
             st = parity.record(workload=w.name + " (batch)", layer=layer, mode="weighted", rule="protect_text", H=w.H,
                                L=w.L, B=w.budget(), M=w.M, **st)
             print(key, st)
