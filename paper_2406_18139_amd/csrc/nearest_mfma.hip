@@ -567,7 +567,16 @@ static int nearest_chunks(int H, int Le, int B)
         const double eff = (double)units / (double)(((units + 767) / 768) * 768);
         if (eff > best_eff + 0.02) { best_eff = eff; best = c; }
     }
-    while (2 * ((tiles + best - 1) / best) > lookm::NEAR_MAX_BLOCKS) ++best;   // two blocks per tile
+    // A chunk of at most 32 blocks has a mark class per block, so the exact pass looks at contenders only, not at
+    // whole classes of blocks: worth more chunks if they fill the machine as evenly.
+    auto blocks = [&](int c) { return 2 * ((tiles + c - 1) / c); };   // two blocks per tile
+    if (blocks(best) > 32)
+        for (int c = best + 1; c <= 8 && tiles / c >= 4; ++c) {
+            const long units = (long)strips * c * H;
+            const double eff = (double)units / (double)(((units + 767) / 768) * 768);
+            if (blocks(c) <= 32 && eff >= best_eff - 0.02) { best = c; break; }
+        }
+    while (blocks(best) > lookm::NEAR_MAX_BLOCKS) ++best;
     return best;
 }
 
