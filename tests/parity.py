@@ -133,6 +133,11 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None, M=Non
     q, k, v, mask = W.generate(w, layer, heads)
     B = w.budget() if B is None else B
     M = w.M if M is None else M
+    return run_and_check_tensors(q, k, v, mask, B, M, mode, rule, label or w.name, layer, oracle_heads)
+
+
+def run_and_check_tensors(q, k, v, mask, B, M, mode, rule="protect_text", label="", layer=0, oracle_heads=None):
+    """The same for inputs made by the caller (CPU tensors q, k, v [H, L, d] and mask [L])."""
     qg, kg, vg, mg = to_gpu(q, k, v, mask)
     H, L, d = q.shape
     ws = lookm.alloc_workspace(H, L, d, B, lookm._dt(qg), qg.device)
@@ -145,7 +150,7 @@ def run_and_check(w, mode, heads=None, layer=0, oracle_heads=None, B=None, M=Non
     assert torch.equal(lean[0], res.kept_idx) and torch.equal(lean[1], res.k_out) and torch.equal(lean[2], res.v_out), \
         "the call without scores_out gives a different cache"
     st = check_outputs(q, k, v, mask, B, M, mode, rule, res, ws, oracle_heads)
-    st = dict(workload=label or w.name, layer=layer, mode=mode, rule=rule, H=H, L=L, B=B, M=M, **st)
+    st = dict(workload=label, layer=layer, mode=mode, rule=rule, H=H, L=L, B=B, M=M, **st)
     return record(**st)
 
 

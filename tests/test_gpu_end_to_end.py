@@ -83,6 +83,53 @@ def test_stack_long_prompts_one_layer_each():
         assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_prompts_end_to_end(seed):
+    """Prompts of random make-up - lengths from a few dozen to three thousand tokens, text and image spans of random
+    lengths (also none of either), any recent window, any feasible budget from "evict every image token" to "evict
+    none", every merge mode, both rules - through the whole path and against the fp64 oracle on every head."""
+    rng = np.random.default_rng(9000 + seed)
+    H, d = int(rng.integers(1, 5)), 128
+    L = int(rng.integers(40, 3000)) if seed % 6 else int(rng.integers(2, 40))
+    mask = np.zeros(L, np.uint8)
+    pos, image = 0, bool(rng.integers(0, 2))
+    while pos < L:
+        span = int(rng.integers(16, 600)) if image else int(rng.integers(1, 40))
+        mask[pos:pos + span] = 1 if image else 0
+        pos += span
+        image = not image
+    if seed % 8 == 3:
+        mask[:] = 1
+    if seed % 8 == 5:
+        mask[:] = 0
+    M = int(rng.integers(0, min(L, 80) + 1))
+    protected = oracle.protected_count(mask, M)
+    B = protected + int(rng.integers(0, L - protected + 1))
+    rule = "protect_text"
+    if seed % 4 == 2 and M < B:                      # the literal rule also below the protected count
+        rule, B = "literal", int(rng.integers(M, L + 1))
+    if B == 0:
+        B = 1 if L > 1 or protected else B
+    mode = "none" if seed % 7 == 6 else ["averaged", "pivotal", "weighted"][seed % 3]
+    g = torch.Generator().manual_seed(9000 + seed)
+    n_cent = int(rng.integers(2, 40))
+    cent_k, cent_v = torch.randn(H, n_cent, d, generator=g), torch.randn(H, n_cent, d, generator=g)
+    which = torch.randint(0, n_cent, (L,), generator=g)
+    img = torch.from_numpy(mask.astype(bool))
+    q = torch.randn(H, L, d, generator=g)
+    k = torch.randn(H, L, d, generator=g)
+    v = torch.randn(H, L, d, generator=g)
+    k[:, img] = cent_k[:, which[img]] + 0.3 * k[:, img]
+    v[:, img] = cent_v[:, which[img]] + 0.3 * v[:, img]
+    q, k, v = (t.to(torch.bfloat16) for t in (q, k, v))
+    B = min(max(B, M, 0), L)
+    if rule == "protect_text" and B < protected:
+        B = protected
+    st = parity.run_and_check_tensors(q, k, v, torch.from_numpy(mask), B, M, mode, rule, label=f"random_{seed}")
+    print(f"random prompt {seed}: H={H} L={L} B={B} M={M} protected={protected} {mode} {rule}", st)
+    assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
+
+
 def test_stack_jobs_at_full_size_through_one_batch_call():
     """The 32-layer x 4-prompt stack at its real shape: 32-head jobs of three of its ragged prompts (4K, 6K and 12K
     tokens), two layers each, built from the host generator and issued through ONE two-stream batch call in the order
