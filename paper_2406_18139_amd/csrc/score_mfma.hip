@@ -148,9 +148,29 @@ constexpr int LIST_HEAD = 64;
 __device__ __forceinline__ void build_key_lists(const uint8_t* __restrict__ mask, int L, int M, int32_t* __restrict__ lists,
                                                 int* scan /* LDS, 256 ints */)
 {
+    // Thread t owns the positions [t * per, t * per + per), per <= LOOKM_MAX_L / 256 = 128.  Their mask bytes are
+    // fetched sixteen at a time, all sixteen loads in flight together (one at a time, a 12 K-token mask cost this
+    // workgroup fifty memory latencies twice over), and kept as 128 flag bits for the second sweep.
+    static_assert(LOOKM_MAX_L <= 256 * 128, "a thread's range must fit its 128 flag bits");
     const int tid = threadIdx.x, per = (L + 255) / 256, lo = min(L, tid * per), hi = min(L, lo + per);
+    uint64_t flags[2] = {0ull, 0ull};
     int nc = 0;
-    for (int j = lo; j < hi; ++j) nc += (mask[j] != 0 && j < L - M) ? 1 : 0;
+#pragma unroll
+    for (int j0 = 0; j0 < 128; j0 += 16) {
+        if (j0 < per) {                                  // uniform
+            uint8_t b[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) b[u] = mask[min(lo + j0 + u, L - 1)];
+            uint32_t w = 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int j = lo + j0 + u;
+                w |= (j < hi && b[u] != 0 && j < L - M) ? (1u << u) : 0u;
+            }
+            flags[j0 >> 6] |= (uint64_t)w << (j0 & 63);
+            nc += __popc(w);
+        }
+    }
     scan[tid] = nc;
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {          // inclusive scan of the competing counts
@@ -162,7 +182,9 @@ __device__ __forceinline__ void build_key_lists(const uint8_t* __restrict__ mask
     int c_at = scan[tid] - nc, p_at = lo - c_at;       // competing / protected keys before this thread's range
     if (tid == 255) { lists[0] = scan[255]; lists[1] = L - scan[255]; }
     for (int j = lo; j < hi; ++j) {
-        if (mask[j] != 0 && j < L - M) lists[LIST_HEAD + c_at++] = j;
+        const int r = j - lo;
+        const bool competing = (((r < 64) ? flags[0] : flags[1]) >> (r & 63)) & 1ull;
+        if (competing) lists[LIST_HEAD + c_at++] = j;
         else lists[LIST_HEAD + L + p_at++] = j;
     }
 }
