@@ -367,6 +367,7 @@ __device__ __forceinline__ double cosine_exact(const bf16_t* __restrict__ a, con
 
 constexpr int NF_THREADS = 256;
 constexpr int NF_ITEMS = 768;     // (evicted key, candidate slot) pairs evaluated exactly per round of a workgroup
+constexpr int NF_GROUPS = NF_ITEMS / 16;
 constexpr int NF_LDS_CHUNKS = 4;  // chunks whose block masks the fold keeps in LDS (further chunks are read again)
 
 // Folds the chunks of every evicted key (value descending, slot ascending): one thread per evicted key.  Where
@@ -375,7 +376,8 @@ constexpr int NF_LDS_CHUNKS = 4;  // chunks whose block masks the fold keeps in 
 // stands: assign[h, e] = its slot, sim[h, e] = the cosine decoded from the centre of the key's truncation interval
 // (|error| < 1.2e-6).  The other keys of the workgroup are decided exactly, together: their threads list the slots
 // of the marked blocks as (key, slot) items in LDS, every thread of the workgroup evaluates items with
-// cosine_exact, and each key's thread then takes the first maximum in slot order and returns its cosine.  A key
+// cosine_exact and folds the result into its key's maximum (LDS atomics: the largest cosine, then the lowest slot
+// that reaches it = the first maximum in slot order).  A key
 // whose best value is not positive (integer order of the bits is not float order there) takes every slot.
 // (few registers and little LDS on purpose: all workgroups of the headline shape are resident at once, so the
 // kernel takes as long as its slowest workgroup, not twice that)
@@ -385,12 +387,15 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                const int32_t* __restrict__ evicted, int L, int B, int Le, int n_strips, int n_chunks, int CT,
                const NearestPartial* __restrict__ part, int32_t* __restrict__ assign, float* __restrict__ sim)
 {
-    __shared__ int item_pos_e[NF_ITEMS];      // position of the item's evicted key, or -1 for an empty entry
-    __shared__ int item_pos_c[NF_ITEMS];      // position of the item's conserved key
-    __shared__ int item_slot[NF_ITEMS];
-    __shared__ double item_s[NF_ITEMS];
+    // items come in groups of 16 (the slots one lane holds of a 32x32 block, or 16 consecutive slots)
+    __shared__ int grp_pos_e[NF_GROUPS];      // position of the group's evicted key, or -1 for an empty entry
+    __shared__ int grp_first[NF_GROUPS];      // first slot (below 2^15) | owner thread << 16 | consecutive slots << 24
+    __shared__ int grp_limit[NF_GROUPS];      // slots from here on do not exist
+    __shared__ unsigned long long item_s[NF_ITEMS];    // the item's cosine, as an integer of the same order
+    __shared__ unsigned long long best_s[NF_THREADS];  // per owner thread: the largest such integer ...
+    __shared__ int best_r[NF_THREADS];                 // ... and the lowest slot that reaches it
     __shared__ uint2 near_m[NF_LDS_CHUNKS][NF_THREADS];      // block counters per key and chunk (both lanes'); 0: chunk out of reach
-    __shared__ int n_items;
+    __shared__ int n_groups;
     const int h = blockIdx.y, tid = threadIdx.x;
     k += (size_t)h * L * ND;
     rnorm += (size_t)h * L;
@@ -450,15 +455,15 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             m[1] = reach ? p.marks[1] : 0u;
         }
     };
-    // Walks through the candidate slots of this thread's key - the 16 slots of every marked block of every chunk
-    // within reach, or every slot when the best value is not positive; slots past the end of the conserved list
-    // are reported as -1 (so that a block always yields 16 entries).  A non-zero counter b stands for the blocks b,
-    // b + n_cls, ... of the chunk, all of which are visited.
+    // Walks through the candidate slots of this thread's key in groups of 16: the slots this lane half holds of
+    // every marked block of every chunk within reach (first slot f: f + 8 * (g / 4) + g % 4, g = 0..15), or runs of
+    // 16 consecutive slots over the whole list when the best value is not positive.  A non-zero counter b stands
+    // for the blocks b, b + n_cls, ... of the chunk, all of which are visited.  visit(first, limit, consecutive).
     constexpr int n_cls = 32 / cbits, cls_shift = cbits >> 1;  // counter number = bit number >> cls_shift
     constexpr uint32_t field = (1u << cbits) - 1u;
-    auto for_each_candidate = [&](auto&& visit) {
+    auto for_each_group = [&](auto&& visit) {
         if (bk <= 0) {
-            for (int s = 0; s < B; ++s) visit(s);
+            for (int s = 0; s < B; s += 16) visit(s, B, 1);
             return;
         }
         for (int c = 0; c < n_chunks; ++c) {
@@ -470,19 +475,17 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 for (uint32_t rest = m[half]; rest != 0u;) {
                     const int cls = (__ffs((int)rest) - 1) >> cls_shift;
                     rest &= ~(field << (cbits * cls));
-                    for (int b = cls; lo + 32 * b < hi; b += n_cls) {
-                        for (int g = 0; g < 16; ++g) {
-                            const int s = lo + 32 * b + 4 * half + 8 * (g >> 2) + (g & 3);
-                            visit(s < hi ? s : -1);
-                        }
-                    }
+                    for (int b = cls; lo + 32 * b < hi; b += n_cls) visit(lo + 32 * b + 4 * half, hi, 0);
                 }
             }
         }
     };
-    int cnt = 0;
+    auto group_slot = [](int first, int consecutive, int g) {
+        return consecutive ? first + g : first + 8 * (g >> 2) + (g & 3);
+    };
+    int cnt = 0;                                  // groups of this thread's key
     if (pending) {
-        if (bk <= 0) cnt = B;
+        if (bk <= 0) cnt = (B + 15) / 16;
         else
             for (int c = 0; c < n_chunks; ++c) {
                 uint32_t m[2];
@@ -493,57 +496,82 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                     for (uint32_t rest = m[half]; rest != 0u;) {
                         const int cls = (__ffs((int)rest) - 1) >> cls_shift;
                         rest &= ~(field << (cbits * cls));
-                        cnt += (cls < nb) ? 16 * ((nb - cls + n_cls - 1) / n_cls) : 0;
+                        cnt += (cls < nb) ? (nb - cls + n_cls - 1) / n_cls : 0;
                     }
             }
     }
+    // binary64 values as unsigned integers of the same order (x < y <=> key(x) < key(y); no cosine is -0.0: the sums
+    // start at +0.0), so that the maximum over a key's items is one LDS atomic per item
+    auto ordered = [](double x) -> unsigned long long {
+        const unsigned long long b = (unsigned long long)__double_as_longlong(x);
+        return (b >> 63) ? ~b : (b | 0x8000000000000000ull);
+    };
+    auto unordered = [](unsigned long long u) -> double {
+        return __longlong_as_double((long long)((u >> 63) ? (u & 0x7fffffffffffffffull) : ~u));
+    };
     while (true) {
-        for (int i = tid; i < NF_ITEMS; i += NF_THREADS) item_pos_e[i] = -1;
-        if (tid == 0) n_items = 0;
+        if (tid < NF_GROUPS) grp_pos_e[tid] = -1;
+        best_s[tid] = 0ull;                   // below the image of every number
+        best_r[tid] = 0x7fffffff;
+        if (tid == 0) n_groups = 0;
         __syncthreads();
-        // keys whose items fit into this round's list write them (whoever reserves first always fits if its count
-        // is at most the capacity; the order of the reservations decides no result)
+        // keys whose groups fit into this round's list write them (whoever reserves first always fits if its count
+        // is at most the capacity; the order of the reservations decides no result): a few LDS stores per key -
+        // the slots of a group and their conserved positions are worked out by the threads that evaluate them
         int base = -1;
-        if (pending && cnt <= NF_ITEMS) {
-            base = atomicAdd(&n_items, cnt);
-            if (base + cnt > NF_ITEMS) base = -1;
+        if (pending && cnt <= NF_GROUPS) {
+            base = atomicAdd(&n_groups, cnt);
+            if (base + cnt > NF_GROUPS) base = -1;
         }
         if (base >= 0) {
             int at = base;
-            for_each_candidate([&](int s) {
-                item_pos_e[at] = (s >= 0) ? pos_e : -1;
-                item_pos_c[at] = kept[max(s, 0)];            // independent loads: one memory latency for all of them
-                item_slot[at] = s;
+            for_each_group([&](int first, int limit, int consecutive) {
+                grp_pos_e[at] = pos_e;
+                grp_first[at] = first | (tid << 16) | (consecutive << 24);
+                grp_limit[at] = limit;
                 ++at;
             });
         }
         __syncthreads();
-        const int n = min(n_items, NF_ITEMS);
+        const int n = 16 * min(n_groups, NF_GROUPS);
         for (int i = tid; i < n; i += NF_THREADS) {
-            const int pe = item_pos_e[i];
-            if (pe >= 0) item_s[i] = cosine_exact(k + (size_t)pe * ND, k + (size_t)item_pos_c[i] * ND);
+            const int e = i >> 4, pe = grp_pos_e[e], packed = grp_first[e];
+            const int slot = group_slot(packed & 0xffff, packed >> 24, i & 15);
+            const bool valid = pe >= 0 && slot < grp_limit[e];
+            unsigned long long c = 0ull;      // an item that does not exist is below every cosine
+            if (valid) {
+                c = ordered(cosine_exact(k + (size_t)pe * ND, k + (size_t)kept[slot] * ND));
+                atomicMax(&best_s[(packed >> 16) & 0xff], c);
+            }
+            item_s[i] = c;
         }
         __syncthreads();
-        if (base >= 0 || (pending && cnt > NF_ITEMS)) {
-            double best_s = 0.0;
-            int best_r = 0x7fffffff;
-            if (base >= 0) {
-                for (int i = base; i < base + cnt; ++i) {
-                    if (item_pos_e[i] < 0) continue;
-                    const double s = item_s[i];
-                    const int r = item_slot[i];
-                    if (best_r == 0x7fffffff || s > best_s || (s == best_s && r < best_r)) { best_s = s; best_r = r; }
-                }
-            } else {
-                // more candidates than a round holds (many keys of equal direction): this thread walks through them alone
-                for_each_candidate([&](int s) {
-                    if (s < 0) return;
-                    const double c = cosine_exact(k + (size_t)pos_e * ND, k + (size_t)kept[s] * ND);
-                    if (best_r == 0x7fffffff || c > best_s || (c == best_s && s < best_r)) { best_s = c; best_r = s; }
-                });
+        for (int i = tid; i < n; i += NF_THREADS) {       // first maximum in slot order: the lowest slot that reaches it
+            const unsigned long long c = item_s[i];
+            if (c != 0ull) {
+                const int packed = grp_first[i >> 4], owner = (packed >> 16) & 0xff;
+                if (c == best_s[owner]) atomicMin(&best_r[owner], group_slot(packed & 0xffff, packed >> 24, i & 15));
             }
-            assign[ev] = (best_r == 0x7fffffff) ? 0 : best_r;
-            sim[ev] = (float)best_s;
+        }
+        __syncthreads();
+        if (base >= 0) {
+            assign[ev] = (best_r[tid] == 0x7fffffff) ? 0 : best_r[tid];
+            sim[ev] = (best_r[tid] == 0x7fffffff) ? 0.f : (float)unordered(best_s[tid]);
+            pending = false;
+        } else if (pending && cnt > NF_GROUPS) {
+            // more candidates than a round holds (many keys of equal direction): this thread walks through them alone
+            double top_s = 0.0;
+            int top_r = 0x7fffffff;
+            for_each_group([&](int first, int limit, int consecutive) {
+                for (int g = 0; g < 16; ++g) {
+                    const int sl = group_slot(first, consecutive, g);
+                    if (sl >= limit) continue;
+                    const double c = cosine_exact(k + (size_t)pos_e * ND, k + (size_t)kept[sl] * ND);
+                    if (top_r == 0x7fffffff || c > top_s || (c == top_s && sl < top_r)) { top_s = c; top_r = sl; }
+                }
+            });
+            assign[ev] = (top_r == 0x7fffffff) ? 0 : top_r;
+            sim[ev] = (float)top_s;
             pending = false;
         }
         if (!__syncthreads_or(pending)) break;
