@@ -44,6 +44,11 @@ __device__ __forceinline__ void load8(const bf16_t* p, float (&o)[8])
     o[4] = __uint_as_float(a.z << 16); o[5] = __uint_as_float(a.z & 0xffff0000u);
     o[6] = __uint_as_float(a.w << 16); o[7] = __uint_as_float(a.w & 0xffff0000u);
 }
+// 1 / sqrt(sum of squares), 0 for a zero key: binary64 square root and division, one rounding to fp32 at the end
+__device__ __forceinline__ float inverse_norm(double sum_of_squares)
+{
+    return (sum_of_squares > 0.0) ? (float)(1.0 / sqrt(sum_of_squares)) : 0.f;
+}
 __device__ __forceinline__ void store8(float* p, const float (&v)[8])
 {
     *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);

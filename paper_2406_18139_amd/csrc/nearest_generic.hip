@@ -12,24 +12,27 @@ namespace lookm {
 
 constexpr int NT_TS = 64;
 
-// rnorm[h, j] = 1 / ||k[h, j, :]||, or 0 when the norm vanishes.  One 8-lane group per row.
+// rnorm[h, j] = 1 / ||k[h, j, :]||, or 0 when the norm vanishes.  One 8-lane group per row.  The squares are summed
+// in binary64 (for bf16 keys every square and, in practice, every partial sum is exact), so that the result is the
+// correctly rounded inverse norm up to one final rounding: the matching on the matrix cores budgets half a unit in
+// the last place for this factor.
 template <typename T>
 __global__ void __launch_bounds__(256) k_rnorm(const T* __restrict__ k, size_t rows, int d, float* __restrict__ rnorm)
 {
     const size_t row = (size_t)blockIdx.x * 32 + (threadIdx.x >> 3);
     const int sub = threadIdx.x & 7;
-    float s = 0.f;
+    double s = 0.0;
     if (row < rows) {
         for (int c0 = sub * 8; c0 < d; c0 += 64) {
             float v[8];
             load8(k + row * d + c0, v);
-            for (int i = 0; i < 8; ++i) s = fmaf(v[i], v[i], s);
+            for (int i = 0; i < 8; ++i) s = fma((double)v[i], (double)v[i], s);
         }
     }
     s += __shfl_xor(s, 1);
     s += __shfl_xor(s, 2);
     s += __shfl_xor(s, 4);
-    if (row < rows && sub == 0) rnorm[row] = (s > 0.f) ? 1.0f / sqrtf(s) : 0.f;
+    if (row < rows && sub == 0) rnorm[row] = inverse_norm(s);
 }
 
 // stage 64 gathered rows of x into LDS as xt[c][r]; list entries past n read as zero rows

@@ -15,11 +15,13 @@
 // relative); equal keys still resolve to the lower slot exactly.  Across blocks, chunks and the lane pair the
 // order is (truncated value descending, slot ascending), and the runner-up's key is carried along.
 //
-// Exact decisions.  The matrix-core value of y differs from the true one by well under one unit (fp32
-// accumulation of exact products, one fp32 inverse norm, one product: a few ulp), so the true maximum can only
-// be a key whose truncated value lies within NEAR_UNITS units of the best one.  Besides the best key, a lane
+// Exact decisions.  The matrix-core value of y differs from the true one by a few ulp (fp32 accumulation of exact
+// products, one inverse norm, one product; more, relative to y, the smaller the cosine: see near_units), so the true
+// maximum can only be a key whose truncated value lies within a band of a few units below the best one - the
+// band of the evicted key, which widens as its best cosine gets smaller.  Besides the best key, a lane
 // therefore keeps (i) the largest runner-up INSIDE a 32x32 block it has seen and (ii) per block class (block
-// number modulo the number of classes: 32, 16 or 8) a count of the blocks whose best value came within NEAR_UNITS units of its running best (all
+// number modulo the number of classes: 32, 16 or 8) a count of the blocks whose best value came within the band
+// of its running best (all
 // cleared whenever the best jumps by more than that, so that at the end the counters cover every block that can
 // still hold a contender; counts rather than bits, because two such blocks may fall into one class).
 // k_nearest_fold takes the matrix-core choice where the winner's block is the only one counted and its runner-up
@@ -45,7 +47,25 @@ typedef __attribute__((ext_vector_type(16))) float nf32x16;
 constexpr int ND = 128, NBS = 256, NBX = 64, NXROW = 128;   // LDS rows are unpadded, chunks swizzled
 static_assert(NBX == 64, "the norms of a tile are staged by wave 0, one row per lane");
 
-constexpr int NEAR_UNITS = 2;   // a runner-up within this many units of the best truncated value: decided exactly
+// How far below the best truncated value a runner-up may lie and still has to be decided exactly: the band, in
+// units of 16 ulp.  The error budget behind it, with u = 2^-24: y = fl(fl(k_e.k_c) * rnorm_c) = exact * (1 + delta);
+// the matrix-core dot product is eight fp32 accumulations of partial sums bounded by sum |a_k b_k| <= |k_e||k_c|,
+// so it is off by at most 8u / cos relative to the dot (measured over two million pairs: 4.1u / cos); the inverse
+// norm, summed in binary64, by 2u; the product by u.  Two values that the kernels tell apart WITHOUT the exact pass
+// have keys at least band + 1 units apart and therefore differ by more than 16 band ulp >= 16 band u relative,
+// which must cover both errors: 2 (8u / cos + 3u) <= 16 band u, i.e. band >= 1 / cos + 0.375 - two units for the
+// similar keys the method is about, more where a key has no similar conserved key.  `cos` may be any lower bound
+// of the evicted key's best cosine: a wider band only sends more keys through the exact pass.  Below COS_MIN
+// (band above NEAR_UNITS_MAX) every slot goes through it.
+constexpr int NEAR_UNITS_MAX = 14;         // the runner-up distance in a partial saturates at 15
+constexpr float COS_MIN = 0.08f;           // 1 / 0.08 + 1.376 < NEAR_UNITS_MAX + 1
+__device__ __forceinline__ int near_units(float cos_lower_bound)
+{
+    // floor(x + 1) >= ceil(x); the factor covers the reciprocal's and the inverse norm's rounding; a NaN or a
+    // value that is not positive fails the comparison
+    const int nu = (int)(__frcp_rn(cos_lower_bound) * 1.0001f + 1.376f);
+    return (cos_lower_bound > COS_MIN) ? min(nu, NEAR_UNITS_MAX) : NEAR_UNITS_MAX;
+}
 
 // partial result of one (evicted strip, chunk), the lane pair that shares an evicted key already merged:
 //   key   (truncated value of the best conserved key) << 4 | how many units the best runner-up inside a block of the
@@ -53,7 +73,7 @@ constexpr int NEAR_UNITS = 2;   // a runner-up within this many units of the bes
 //   slot  the best key's slot
 //   marks per lane of the pair (first: slots 0-3 of every eight, second: slots 4-7) a word of 32 / w counters of
 //         w bits: counter b = how many of the blocks b, b + 32 / w, ... of the chunk can hold a key within
-//         NEAR_UNITS units of the chunk's best value (a COUNT, so that two such blocks of one class are still seen
+//         the band (near_units) of the chunk's best value (a COUNT, so that two such blocks of one class are still seen
 //         as two); zero for a lane whose own best value is farther away than that.  w = 1, 2 or 4 is the
 //         narrowest width whose counters can count all blocks of a class (near_counter_bits): a chunk of up to
 //         32 blocks has a class per block.
@@ -139,6 +159,7 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     // prologue is two round trips to memory - positions, then rows - instead of one per branch.
     const int ev0 = min(w0 + n, Le - 1), ev1 = min(w0 + 32 + n, Le - 1);
     const int pos0 = evicted[ev0], pos1 = evicted[ev1];
+    const float rn_e[2] = {rnorm[pos0], rnorm[pos1]};   // for the bands: cosine = y / |k_e|
     const int x_begin = chunk * CT, x_end = min(B, x_begin + CT);
     const int n_it = (x_end - x_begin + NBX - 1) / NBX;
     const int ld_row = tid >> 4, ld_chunk = tid & 15;
@@ -194,7 +215,9 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
 
     // per stationary row of this lane; the initial state is below every key and decodes to slot 0
     constexpr int KEY_MIN = (int)0x80000000;
-    constexpr int NEAR_KEY = (NEAR_UNITS << 4) + 15;   // NEAR_UNITS units, in keys (whose low 4 bits are tags)
+    // the band of each of this lane's two evicted keys, in keys (whose low 4 bits are tags): from the running best
+    // value, so it starts at its widest and narrows as better keys appear (a band wider than needed is harmless)
+    int near_key[2] = {(NEAR_UNITS_MAX << 4) + 15, (NEAR_UNITS_MAX << 4) + 15};
     int bkey[2] = {KEY_MIN | 15, KEY_MIN | 15};   // best key (low 4 bits: 15 - entry number)
     int bsec[2] = {KEY_MIN, KEY_MIN};             // largest runner-up inside one block
     int bxb[2] = {0, 0};                          // slot of entry 0 of the block the best key came from
@@ -228,6 +251,13 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         if (it + 1 < n_it) {
             LOOKM_LOAD_TILE(nxt);                // rows of tile it+1 (positions fetched one iteration ago)
             LOOKM_LOAD_INDEX(x0 + 2 * NBX);      // positions of tile it+2
+        }
+        // The bands follow the running best values: after the first tile, where the best moves most, then every
+        // fourth tile (the lower edge of the best key's truncation interval is a lower bound of y).
+        if (it == 1 || (it > 0 && (it & 3) == 0)) {
+#pragma unroll
+            for (int cb = 0; cb < 2; ++cb)
+                near_key[cb] = (near_units(__uint_as_float((uint32_t)bkey[cb] & 0xfffffff0u) * rn_e[cb]) << 4) + 15;
         }
 #pragma unroll 1
         for (int rb = 0; rb < 2; ++rb) {
@@ -271,8 +301,8 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 // a jump by more than the band leaves every earlier block out of reach; a block within the band of
                 // the running best (from either side) stays a candidate
                 const int ahead = __builtin_elementwise_sub_sat(bm, bkey[cb]);   // saturating: the first block's lead is huge
-                bnear[cb] = (ahead > NEAR_KEY) ? 0u : bnear[cb];
-                bnear[cb] += (ahead >= -NEAR_KEY) ? blk_one : 0u;   // cannot overflow: see near_counter_bits
+                bnear[cb] = (ahead > near_key[cb]) ? 0u : bnear[cb];
+                bnear[cb] += (ahead >= -near_key[cb]) ? blk_one : 0u;   // cannot overflow: see near_counter_bits
                 bsec[cb] = max(bsec[cb], bs2);
                 bkey[cb] = better ? bm : bkey[cb];
                 bxb[cb] = better ? xb : bxb[cb];
@@ -302,8 +332,9 @@ k_nearest_mfma(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
         uint32_t theirs = (uint32_t)__shfl_xor((int)mine, 32);
         const bool other = ohi > hi || (ohi == hi && oslot < slot);
         // the losing lane's blocks only matter if its best value is within the band of the winner's
-        if (other) mine = (hi >= ohi - NEAR_UNITS) ? mine : 0u;
-        else theirs = (ohi >= hi - NEAR_UNITS) ? theirs : 0u;
+        const int band = max(near_key[cb], __shfl_xor(near_key[cb], 32)) >> 4;   // the wider of the pair's bands
+        if (other) mine = (hi >= ohi - band) ? mine : 0u;
+        else theirs = (ohi >= hi - band) ? theirs : 0u;
         if (other) { hi = ohi; slot = oslot; sec = osec; }
         if (half == 0) {
             NearestPartial p;
@@ -371,14 +402,15 @@ constexpr int NF_GROUPS = NF_ITEMS / 16;
 constexpr int NF_LDS_CHUNKS = 4;  // chunks whose block masks the fold keeps in LDS (further chunks are read again)
 
 // Folds the chunks of every evicted key (value descending, slot ascending): one thread per evicted key.  Where
-// the winner's block is the only marked block of all chunks whose best value is within NEAR_UNITS units of the
+// the winner's block is the only marked block of all chunks whose best value is within the key's band of the
 // overall best, and the winner's lane saw no runner-up inside a block within that distance, the matrix-core choice
 // stands: assign[h, e] = its slot, sim[h, e] = the cosine decoded from the centre of the key's truncation interval
 // (|error| < 1.2e-6).  The other keys of the workgroup are decided exactly, together: their threads list the slots
 // of the marked blocks as (key, slot) items in LDS, every thread of the workgroup evaluates items with
 // cosine_exact and folds the result into its key's maximum (LDS atomics: the largest cosine, then the lowest slot
 // that reaches it = the first maximum in slot order).  A key
-// whose best value is not positive (integer order of the bits is not float order there) takes every slot.
+// whose best value is not positive (integer order of the bits is not float order there), or whose best cosine is
+// below COS_MIN, takes every slot.
 // (few registers and little LDS on purpose: all workgroups of the headline shape are resident at once, so the
 // kernel takes as long as its slowest workgroup, not twice that)
 template <int cbits>   // counter width of the mark words (near_counter_bits of the chunk length)
@@ -406,7 +438,8 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     const int ev = blockIdx.x * NF_THREADS + tid;
 
     bool pending = false;                     // this thread's key still needs the exact decision
-    int pos_e = 0, bk = 0;
+    bool all_slots = false;                   // ... over every slot: its best value is too small to trust any order
+    int pos_e = 0, bk = 0, band = NEAR_UNITS_MAX;
     const NearestPartial* mine = part;        // this key's partial of chunk 0; chunk c is n_strips * NBS entries further
     if (ev < Le) {
         pos_e = evicted[ev];
@@ -425,19 +458,26 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
                 if (key[c] > bk || (key[c] == bk && p.slot < bs)) { bk = key[c]; bs = p.slot; bd = p.key & 15; }
             }
         }
+        // this key's band, from the lower edge of its best key's truncation interval
+        const float rn_e = rnorm[pos_e], cos_low = __uint_as_float((uint32_t)bk << 4) * rn_e;
+        band = near_units(cos_low);
         int marked = 0;
 #pragma unroll
         for (int c = 0; c < NEAR_MAX_CHUNKS; ++c) {
-            const bool reach = key[c] >= bk - NEAR_UNITS;          // chunks within reach only
+            const bool reach = key[c] >= bk - band;                // chunks within reach only
             marked += reach ? marks[c] : 0;
             if (c < NF_LDS_CHUNKS && c < n_chunks && !reach) near_m[c][tid] = make_uint2(0u, 0u);
         }
-        // bk <= 0: the best value is zero or negative; every slot is a candidate then
-        pending = bk <= 0 || bd <= NEAR_UNITS || marked > 1;
+        // the best value is zero or negative (the integer order of the bits is not the order of the values there),
+        // or the best cosine is so small that the rounding errors of the dot products, which grow like 1 / cos in
+        // units of the value, may exceed the band: every slot is a candidate then
+        const float y = __uint_as_float(((uint32_t)bk << 4) | 8u);         // (k_e.k_c) * rnorm_c, centre of the interval
+        const float cos_best = y * rn_e;
+        all_slots = bk <= 0 || !(cos_low > COS_MIN);
+        pending = all_slots || bd <= band || marked > 1;
         if (!pending) {
-            const float y = __uint_as_float(((uint32_t)bk << 4) | 8u);     // (k_e.k_c) * rnorm_c, centre of the interval
             assign[ev] = min(max(bs, 0), B - 1);
-            sim[ev] = y * rnorm[pos_e];
+            sim[ev] = cos_best;
         }
     }
     if (!__syncthreads_or(pending)) return;
@@ -450,7 +490,7 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
             m[1] = both.y;
         } else {                                                       // more chunks than LDS holds: read again
             const NearestPartial p = mine[(size_t)c * n_strips * NBS];
-            const bool reach = (p.key >> 4) >= bk - NEAR_UNITS;
+            const bool reach = (p.key >> 4) >= bk - band;
             m[0] = reach ? p.marks[0] : 0u;
             m[1] = reach ? p.marks[1] : 0u;
         }
@@ -462,7 +502,7 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     constexpr int n_cls = 32 / cbits, cls_shift = cbits >> 1;  // counter number = bit number >> cls_shift
     constexpr uint32_t field = (1u << cbits) - 1u;
     auto for_each_group = [&](auto&& visit) {
-        if (bk <= 0) {
+        if (all_slots) {
             for (int s = 0; s < B; s += 16) visit(s, B, 1);
             return;
         }
@@ -485,7 +525,7 @@ k_nearest_fold(const bf16_t* __restrict__ k, const float* __restrict__ rnorm, co
     };
     int cnt = 0;                                  // groups of this thread's key
     if (pending) {
-        if (bk <= 0) cnt = (B + 15) / 16;
+        if (all_slots) cnt = (B + 15) / 16;
         else
             for (int c = 0; c < n_chunks; ++c) {
                 uint32_t m[2];

@@ -363,10 +363,10 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         // and the stage call lookm_nearest reproduces the matching of the whole path exactly.
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-            float part[4];   // partial sums number 2*j + half
+            double part[4];   // partial sums number 2*j + half, in binary64 as in k_rnorm
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float ss = 0.f;
+                double ss = 0.0;
 #pragma unroll
                 for (int rep = 0; rep < 2; ++rep) {
                     const uint4 v = __builtin_bit_cast(uint4, sf[cb][j + 4 * rep]);
@@ -374,19 +374,19 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
                         const float lo = __uint_as_float(w4[i] << 16), hi = __uint_as_float(w4[i] & 0xffff0000u);
-                        ss = fmaf(lo, lo, ss);
-                        ss = fmaf(hi, hi, ss);
+                        ss = fma((double)lo, (double)lo, ss);
+                        ss = fma((double)hi, (double)hi, ss);
                     }
                 }
                 part[j] = ss;
             }
-            float pair[4];
+            double pair[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) pair[j] = part[j] + __shfl_xor(part[j], 32);
-            const float ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
+            const double ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
             // the row's position again: from LDS on the sparse path (not held in a register since the fragment loads)
             const int row = sparse ? spos[cb * 256 + tid] : w0 + cb * 32 + n;
-            if (half == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
+            if (half == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = inverse_norm(ss);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
@@ -567,18 +567,18 @@ k_score_combine(int group, int L, int R0, int C, const float* __restrict__ part_
         for (int idx = (tile - nS) * 32 + (r >> 3); idx < NP; idx += 32 * nS) {     // uniform per group of eight lanes
             const int pos = lists[LIST_HEAD + L + idx];
             const bf16_t* row = k + ((size_t)h * L + pos) * SD;
-            float ss = 0.f;
+            double ss = 0.0;
 #pragma unroll
             for (int rep = 0; rep < 2; ++rep) {
                 float v[8];
                 load8(row + sub * 8 + rep * 64, v);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) ss = fmaf(v[i], v[i], ss);
+                for (int i = 0; i < 8; ++i) ss = fma((double)v[i], (double)v[i], ss);
             }
             ss += __shfl_xor(ss, 1);
             ss += __shfl_xor(ss, 2);
             ss += __shfl_xor(ss, 4);
-            if (sub == 0) rnorm[(size_t)h * L + pos] = (ss > 0.f) ? 1.0f / sqrtf(ss) : 0.f;
+            if (sub == 0) rnorm[(size_t)h * L + pos] = inverse_norm(ss);
         }
         return;
     }

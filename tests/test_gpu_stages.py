@@ -350,6 +350,33 @@ def test_nearest_near_ties_between_far_apart_blocks(H, Le):
     np.testing.assert_allclose(s[0][rows], rs, rtol=0, atol=parity.SIM_ATOL)
 
 
+@pytest.mark.parametrize("B,Le", [(1024, 4000), (64, 3000), (8, 2000), (2, 600)])
+def test_nearest_keys_without_a_similar_conserved_key(B, Le):
+    """Evicted keys unrelated to every conserved key: best cosines of 0.35 (1024 conserved keys) down to 0.1 (two).
+    The rounding errors of the fp32 dot products grow like 1 / cos relative to the value, so the band inside which
+    the matching is decided exactly widens with them, and below a cosine of 0.08 every slot is decided exactly.
+    Every conserved key has a twin 2^-14 away in the dot product, so near ties are the rule here; every row must
+    still get the binary64 answer."""
+    d = 128
+    g = torch.Generator().manual_seed(B)
+    half = torch.randn(B // 2, d, generator=g)
+    half[:, 5] = 0
+    twin = half.clone()
+    twin[:, 5] = 2.0 ** -7
+    kept_k = torch.cat([half, twin])
+    ev_k = torch.randn(Le, d, generator=g)
+    ev_k[:, 5] = (2.0 ** -7) * (1 - 2 * (torch.arange(Le) % 2)).float()
+    k = torch.cat([kept_k, ev_k])[None].to(torch.bfloat16)
+    kept = np.arange(B, dtype=np.int32)[None]
+    ev = np.arange(B, B + Le, dtype=np.int32)[None]
+    a, s = lookm.lookm_nearest(k.cuda(), torch.from_numpy(kept).cuda(), torch.from_numpy(ev).cuda())
+    a, s = a.cpu().numpy()[0], s.cpu().numpy()[0]
+    ra, rs = oracle.nearest(k[0].float().numpy(), kept[0], ev[0])
+    print(f"dissimilar keys, B={B}: best cosines {rs.min():.3f} .. {rs.max():.3f}, {int(np.sum(a != ra))} rows differ")
+    assert np.array_equal(a, ra)
+    np.testing.assert_allclose(s, rs, rtol=0, atol=parity.SIM_ATOL)
+
+
 @pytest.mark.parametrize("H,B,Le", [(16, 2048, 12288), (32, 3072, 9216), (2, 1000, 3000)])
 def test_nearest_near_ties_scattered_over_the_conserved_axis(H, B, Le):
     """Near-tied conserved keys at random slots (any lane, any entry of a block, any chunk; some in threes), with
