@@ -161,6 +161,10 @@ int lookm_select(const float* scores, const uint8_t* modality_mask, int H, int L
  * Eq. 9: for every evicted position e of head h, the slot r in [0, budget) of the conserved key with
  * the highest cosine similarity to key e (original keys; ties -> lower slot, i.e. lower position;
  * a zero-norm key has cosine 0 with everything), and that cosine.
+ *   For bf16 keys of 128 dims the choice is the one the definition gives when every cosine is evaluated in binary64
+ *   (sums over the dims in order, square roots, one product, one division; first maximum in slot order): the matrix
+ *   cores find the candidates, and every candidate that their fp32 values cannot tell from the best is evaluated
+ *   again that way.  Other shapes compare fp32 cosines.
  *   kept_idx, evicted_idx  device, as produced by lookm_select (in-range, ascending).
  *   assign  device, int32 [H, L - budget].   sim  device, float [H, L - budget].
  */
