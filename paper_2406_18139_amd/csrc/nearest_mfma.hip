@@ -21,15 +21,14 @@
 // band of the evicted key, which widens as its best cosine gets smaller.  Besides the best key, a lane
 // therefore keeps (i) the largest runner-up INSIDE a 32x32 block it has seen and (ii) per block class (block
 // number modulo the number of classes: 32, 16 or 8) a count of the blocks whose best value came within the band
-// of its running best (all
-// cleared whenever the best jumps by more than that, so that at the end the counters cover every block that can
-// still hold a contender; counts rather than bits, because two such blocks may fall into one class).
-// k_nearest_fold takes the matrix-core choice where the winner's block is the only one counted and its runner-up
-// inside the block is farther away; every other evicted key (one in six hundred at the headline shape) is decided again
-// exactly: the slots of every block of the classes counted are evaluated in binary64 with a fixed arithmetic contract -
-// sequential sums over k = 0..d-1 of products that are exact in binary64, binary64 square roots, one product,
-// one division, first maximum in slot order - which is a definition, not an approximation, so any
-// implementation of the same contract takes the same decision.
+// of its running best (all cleared whenever the best jumps by more than that, so that at the end the counters
+// cover every block that can still hold a contender; counts rather than bits, because two such blocks may fall
+// into one class).  k_nearest_fold takes the matrix-core choice where the winner's block is the only one counted
+// and its runner-up inside the block is farther away; every other evicted key (one in six hundred at the headline
+// shape) is decided again exactly: the slots of every block of the classes counted are evaluated in binary64 with
+// a fixed arithmetic contract - sequential sums over k = 0..d-1 of products that are exact in binary64, binary64
+// square roots, one product, one division, first maximum in slot order - which is a definition, not an
+// approximation, so any implementation of the same contract takes the same decision.
 //
 // The conserved axis is cut into chunks (one workgroup per (evicted strip, chunk)) chosen so that the
 // number of workgroups fills the resident slots evenly; enumeration is chunk-major and XCD-affine as in
