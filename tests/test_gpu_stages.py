@@ -258,6 +258,7 @@ def split(L, B, seed):
     (2, 600, 64, 128, torch.bfloat16),
     (1, 300, 1, 128, torch.bfloat16),      # one conserved key
     (1, 300, 299, 128, torch.bfloat16),    # one evicted key
+    (1, 32768, 32000, 128, torch.bfloat16),  # the longest prompt the library takes, nearly all of it conserved: nine chunks of 112 blocks
     (2, 500, 130, 64, torch.bfloat16),     # portable path
     (2, 256, 154, 64, torch.float32),
     (1, 100, 30, 8, torch.float32),
