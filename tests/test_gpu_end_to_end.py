@@ -130,6 +130,54 @@ def test_random_prompts_end_to_end(seed):
     assert st["kept_diff_heads"] == 0 and st["nearest_tie_rows"] == 0
 
 
+def test_longest_prompt_the_library_takes():
+    """L = LOOKM_MAX_L = 32768 (one head): every size-dependent limit at once - 128 positions per thread in the key
+    lists of the sparse second pass, 128 strips, the longest chunks.  The fp64 oracle's score loop would take minutes
+    here, so the scores are checked by what holds at any size (they sum to L; the call without scores_out gives the
+    same cache bit for bit), the selection and the merge stage by stage on the kernel's own intermediate results,
+    and the matching against the oracle on a sample of the evicted keys."""
+    L, d, M = 32768, 128, 64
+    rng = np.random.default_rng(32768)
+    mask = np.ones(L, np.uint8)
+    pos = 0
+    while pos < L:                                   # text spans of 5..40 tokens between images of 576
+        span = int(rng.integers(5, 40))
+        mask[pos:pos + span] = 0
+        pos += span + 576
+    protected = oracle.protected_count(mask, M)
+    B = protected + (L - protected) // 5
+    g = torch.Generator().manual_seed(32768)
+    cent = torch.randn(2, 48, d, generator=g)
+    which = torch.randint(0, 48, (L,), generator=g)
+    img = torch.from_numpy(mask.astype(bool))
+    q, k, v = (torch.randn(1, L, d, generator=g) for _ in range(3))
+    k[0, img] = cent[0, which[img]] + 0.3 * k[0, img]
+    v[0, img] = cent[1, which[img]] + 0.3 * v[0, img]
+    q, k, v = (t.to(torch.bfloat16) for t in (q, k, v))
+    dev = torch.device("cuda:0")
+    qg, kg, vg, mg = (t.to(dev) for t in (q, k, v, torch.from_numpy(mask)))
+    ws = lookm.alloc_workspace(1, L, d, B, lookm.BF16, dev)
+    lean = lookm.lookm_compress(qg, kg, vg, mg, B, M, "weighted", want_scores=False, workspace=ws)
+    lean = (lean.kept_idx.clone(), lean.k_out.clone(), lean.v_out.clone())
+    res = lookm.lookm_compress(qg, kg, vg, mg, B, M, "weighted", want_scores=True, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(lean[0], res.kept_idx) and torch.equal(lean[1], res.k_out) and torch.equal(lean[2], res.v_out)
+    scores = res.scores.cpu().numpy()
+    np.testing.assert_allclose(scores.astype(np.float64).sum(), L, rtol=2e-5)
+    kept = res.kept_idx.cpu().numpy()
+    ev = lookm.workspace_view(ws, "evicted", 1, 1, L, d, B, lookm.BF16).cpu().numpy()
+    assign = lookm.workspace_view(ws, "assign", 1, 1, L, d, B, lookm.BF16).cpu().numpy()
+    sim = lookm.workspace_view(ws, "sim", 1, 1, L, d, B, lookm.BF16).cpu().numpy()
+    parity.check_select_stage(kept, ev, scores, mask, B, M)
+    rows = np.arange(0, L - B, 41)
+    ra, rs = oracle.nearest(k[0].float().numpy(), kept[0], ev[0][rows])
+    assert np.array_equal(assign[0][rows], ra)
+    np.testing.assert_allclose(sim[0][rows], rs, rtol=0, atol=parity.SIM_ATOL)
+    for x, o in ((k, res.k_out), (v, res.v_out)):
+        parity.check_merge(x[0].float().numpy(), kept[0], ev[0], assign[0], sim[0], "weighted", o[0].float().cpu().numpy(),
+                           torch.bfloat16)
+
+
 def test_stack_jobs_at_full_size_through_one_batch_call():
     """The 32-layer x 4-prompt stack at its real shape: 32-head jobs of three of its ragged prompts (4K, 6K and 12K
     tokens), two layers each, built from the host generator and issued through ONE two-stream batch call in the order
