@@ -3,12 +3,18 @@
 // Both passes are the same machine with the roles of Q and K swapped.  A workgroup (4 waves)
 // owns 256 "stationary" rows - query rows in pass 1, key rows in pass 2 - whose MFMA B-operand
 // fragments stay in registers (64 rows x 128 dims per wave = 64 VGPRs), and streams the other
-// tensor past them in 64-row tiles through double-buffered LDS as the A operand.  With
-// v_mfma_f32_32x32x16_bf16 a lane's 16 accumulator values then belong to ONE stationary row and
-// 16 streamed rows, so both reductions of the method are in-lane:
+// tensor past them in 64-row tiles through double-buffered LDS as the A operand.  The MFMA is
+// v_mfma_f32_16x16x32_bf16: a 32-row block of the streamed tensor against the wave's 64 stationary rows is
+// eight 16x16 tiles (two groups of 16 streamed rows x four groups of 16 stationary rows), and of every tile a
+// lane (c = lane % 16, q = lane / 16) holds the streamed rows 4q .. 4q+3 against stationary row c.  A lane's
+// 32 accumulator values of a block thus belong to FOUR stationary rows, eight streamed rows each, and both
+// reductions of the method stay in-lane:
 //   pass 1: running (max, sum) of 2^(c q.k) over the keys of a query row   -> lse2[i]
 //   pass 2: running sum of 2^(c q.k - lse2[i]) over the query rows of a key -> A_s[j]
-// The two lanes that share a stationary row (lane, lane^32) are combined once, after the loop.
+// The four lanes that share a stationary row (equal c) are combined once, after the loop.  (The 32x32x16 form
+// of the instruction, with which a lane holds 16 streamed rows of two stationary rows, does the same work in
+// the same registers, but this chip sustains 13 % less of it under this load, measured with random operands;
+// with the epilogues the two score passes together are 6 % faster this way.)
 // Nothing is atomically accumulated; every sum has a fixed order, so results are bitwise
 // repeatable.  c = log2(e)/sqrt(d) folds the softmax scale into the exp2 argument.
 #include "common.h"
@@ -19,7 +25,7 @@
 namespace lookm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int SD = 128;        // head dim
 constexpr int BS = 256;        // stationary rows per workgroup
@@ -30,76 +36,82 @@ constexpr int XROW = 128;       // LDS row = 256 B, unpadded; the 16-byte chunk 
 
 __device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// Epilogues of the two 32x32 blocks a wave finishes together: the same 32 streamed rows against its two sets of 32
-// stationary rows.  A lane's 16 accumulator entries are 16 streamed rows against ONE stationary row, entry r being
-// streamed row xb + 8*(r/4) + r%4.
-//   PASS 2: running sums of 2^(c*(s - b_i)) over the query rows of the lane's two keys, b_i = lse2_i / c; the
+// Epilogues of a finished block: acc[rg][cg], rg = which 16 of the block's 32 streamed rows, cg = which 16 of the
+// wave's 64 stationary rows.  Entry i of acc[rg][cg] is streamed row xq + 16*rg + i (xq = block start + 4q) against
+// this lane's stationary row of group cg, whose position is sP[cg].
+//   PASS 2: running sums of 2^(c*(s - b_i)) over the query rows of the lane's four keys, b_i = lse2_i / c; the
 //           accumulators arrive with -b_i already in them (the MFMA chain starts from it instead of from zero),
 //           so no per-row value has to be held in registers here.
 template <bool MASK>
-__device__ __forceinline__ void colsum_pair_epilogue(const f32x16& X, const f32x16& Y, float scale2, int xb, int sA,
-                                                     int sB, float (&run)[2])
+__device__ __forceinline__ void colsum_block_epilogue(const f32x4 (&acc)[2][4], float scale2, int xq, const int (&sP)[4],
+                                                      float (&run)[4])
 {
-    float sx = 0.f, sy = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float px = __builtin_amdgcn_exp2f(X[r] * scale2);
-        float py = __builtin_amdgcn_exp2f(Y[r] * scale2);
-        if (MASK && (xb + 8 * (r >> 2) + (r & 3) < sA)) px = 0.f;   // query before the key
-        if (MASK && (xb + 8 * (r >> 2) + (r & 3) < sB)) py = 0.f;
-        sx += px;
-        sy += py;
+    for (int cg = 0; cg < 4; ++cg) {
+        float sum;   // (started from its first term: 0 + x is an addition the compiler may not drop)
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float p = __builtin_amdgcn_exp2f(acc[rg][cg][i] * scale2);
+                if (MASK && (xq + 16 * rg + i < sP[cg])) p = 0.f;   // query before the key
+                sum = (rg == 0 && i == 0) ? p : sum + p;
+            }
+        run[cg] += sum;
     }
-    run[0] += sx;
-    run[1] += sy;
 }
 
-// Pass 1, the two finished blocks of a wave (same 32 streamed keys against its two sets of 32 query rows).
+// Pass 1, a finished block (32 streamed keys against the lane's four query rows).
 // The reference of a running sum is refreshed lazily: a block is first summed against the row's current reference m;
 // only if a sum overflows (the first block of a row, where m is still "minus infinity", or a logit more than 64
 // binades above the reference) is the block maximum taken and the running sum rescaled.  The result is the same up
 // to rounding - a float sum keeps its relative precision at any magnitude below 2^64 - and the common case saves
-// the maximum over the block.  One wave-uniform test covers both blocks (a branch on a vector result drains the
-// wave's vector pipeline, so there is one per pair, not one per block); the refresh is valid for a block that did
-// not overflow as well.
-__device__ __forceinline__ void lse_refresh(const f32x16& acc, float scale2, float& m, float& l)
+// the maximum over the block.  One wave-uniform test covers the whole block (a branch on a vector result drains the
+// wave's vector pipeline); the refresh is valid for a row that did not overflow as well.
+__device__ __forceinline__ void lse_refresh(const f32x4& lo, const f32x4& hi, float scale2, float& m, float& l)
 {
-    float bm = fmaxf(fmaxf(acc[0], acc[1]), acc[2]);
-#pragma unroll
-    for (int r = 3; r < 15; r += 2) bm = fmaxf(fmaxf(bm, acc[r]), acc[r + 1]);
-    bm = fmaxf(bm, acc[15]);
+    const float bm = fmaxf(fmaxf(fmaxf(fmaxf(lo[0], lo[1]), lo[2]), fmaxf(fmaxf(lo[3], hi[0]), hi[1])), fmaxf(hi[2], hi[3]));
     const float mn = fmaxf(m, bm * scale2);
     float sum = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sum += __builtin_amdgcn_exp2f(fmaf(acc[r], scale2, -mn));
+    for (int i = 0; i < 4; ++i) sum += __builtin_amdgcn_exp2f(fmaf(lo[i], scale2, -mn));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sum += __builtin_amdgcn_exp2f(fmaf(hi[i], scale2, -mn));
     l = fmaf(l, __builtin_amdgcn_exp2f(m - mn), sum);
     m = mn;
 }
 
 template <bool MASK>
-__device__ __forceinline__ void lse_pair_epilogue(f32x16 X, f32x16 Y, float scale2, int xb, int sA, int sB,
-                                                  float (&m)[2], float (&l)[2])
+__device__ __forceinline__ void lse_block_epilogue(f32x4 (&acc)[2][4], float scale2, int xq, const int (&sP)[4],
+                                                   float (&m)[4], float (&l)[4])
 {
     if (MASK) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int key = xb + 8 * (r >> 2) + (r & 3);
-            if (key > sA) X[r] = -INFINITY;   // key after the query
-            if (key > sB) Y[r] = -INFINITY;
-        }
-    }
-    float sx = 0.f, sy = 0.f;
+        for (int cg = 0; cg < 4; ++cg)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        sx += __builtin_amdgcn_exp2f(fmaf(X[r], scale2, -m[0]));
-        sy += __builtin_amdgcn_exp2f(fmaf(Y[r], scale2, -m[1]));
+            for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (xq + 16 * rg + i > sP[cg]) acc[rg][cg][i] = -INFINITY;   // key after the query
     }
-    if (__builtin_expect(__any(!(sx <= 1.8e19f) || !(sy <= 1.8e19f)), 0)) {     // also true for NaN; wave-uniform
-        lse_refresh(X, scale2, m[0], l[0]);
-        lse_refresh(Y, scale2, m[1], l[1]);
+    float sum[4];
+#pragma unroll
+    for (int cg = 0; cg < 4; ++cg) {
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(acc[rg][cg][i], scale2, -m[cg]));
+                sum[cg] = (rg == 0 && i == 0) ? p : sum[cg] + p;   // (0 + x is an addition the compiler may not drop)
+            }
+    }
+    const bool over = !(sum[0] <= 1.8e19f) || !(sum[1] <= 1.8e19f) || !(sum[2] <= 1.8e19f) || !(sum[3] <= 1.8e19f);
+    if (__builtin_expect(__any(over), 0)) {     // also true for NaN; wave-uniform
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) lse_refresh(acc[0][cg], acc[1][cg], scale2, m[cg], l[cg]);
     } else {
-        l[0] += sx;
-        l[1] += sy;
+#pragma unroll
+        for (int cg = 0; cg < 4; ++cg) l[cg] += sum[cg];
     }
 }
 
@@ -210,7 +222,7 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     __shared__ __attribute__((aligned(16))) bf16_t xs1[BX * XROW];
     __shared__ __attribute__((aligned(16))) float xl0[BX];   // pass 2: -lse2[i] of the streamed query rows
     __shared__ __attribute__((aligned(16))) float xl1[BX];
-    __shared__ int spos[SPARSE ? 2 * 256 : 1];   // sparse pass 2: positions of every lane's two stationary rows
+    __shared__ int spos[SPARSE ? 4 * 256 : 1];   // sparse pass 2: positions of every lane's four stationary rows
 
     // pass 1 with a mask: the launch has one workgroup more, which builds the key lists for pass 2
     if (PASS == 1 && modality != nullptr && blockIdx.x == gridDim.x - 1) {
@@ -260,8 +272,8 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
     // the wave number is uniform across a wave: taken through a scalar register, everything derived from it (the
     // wave's first row, loop bounds, LDS addresses) stays in scalar registers and scalar branches
-    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, half = lane >> 5,
-              n = lane & 31;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, q4 = lane >> 4,
+              c16 = lane & 15;   // this lane: column c16 of every 16x16 tile, rows 4*q4 .. 4*q4+3
     const int w0 = s0 + wave * 64;
 
     // The strip's first row decides where its streamed range starts (sparse: a list entry).
@@ -274,32 +286,34 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     // tile and writes partials that nothing reads (an early exit here costs the kernel its register budget)
     const bool idle = sparse && (s0 >= NC || x_end <= x_begin);
 
-    // Positions of this lane's two stationary rows (cb = 0, 1) and of the wave's first and last row: row numbers
-    // themselves on the dense path, list entries on the sparse one (rows past the end of the list: a position past
-    // the prompt, which no query row reaches).
-    int sA = w0 + n, sB = w0 + 32 + n, p_wave_lo = w0, p_wave_hi = w0 + 63;
+    // Positions of this lane's four stationary rows (row 16*cg + c16 of the wave, cg = 0..3) and of the wave's first
+    // and last row: row numbers themselves on the dense path, list entries on the sparse one (rows past the end of the
+    // list: a position past the prompt, which no query row reaches).
+    int p_wave_lo = w0, p_wave_hi = w0 + 63;
     if (sparse) {
-        sA = (w0 + n < NC) ? clist[w0 + n] : 0x3fffffff;
-        sB = (w0 + 32 + n < NC) ? clist[w0 + 32 + n] : 0x3fffffff;
         // wave-uniform values: kept in scalar registers
         p_wave_lo = (w0 < NC) ? __builtin_amdgcn_readfirstlane(clist[min(w0, NC - 1)]) : 0x3fffffff;
         p_wave_hi = (w0 < NC) ? __builtin_amdgcn_readfirstlane(clist[min(w0 + 63, NC - 1)]) : 0x3fffffff;
-        // the per-lane positions are only needed again where a tile touches the diagonal: parked in LDS meanwhile
-        // (each lane reads back what it wrote itself, so no barrier is involved)
-        spos[tid] = sA;
-        spos[256 + tid] = sB;
     }
+    // the position of stationary row cg of this lane (sparse: from LDS, see below)
+    auto stationary_pos = [&](int cg) { return sparse ? spos[cg * 256 + tid] : w0 + 16 * cg + c16; };
 
-    // stationary fragments: lane holds row sA / sB, dims ks*16 + half*8 .. +7
-    bf16x8 sf[2][8];
+    // stationary fragments: of row 16*cg + c16, the dims 32*ks + 8*q4 .. +7 (the B operand of MFMA step ks)
+    bf16x8 sf[4][4];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int row = cb ? sB : sA;
+    for (int cg = 0; cg < 4; ++cg) {
+        int row = w0 + 16 * cg + c16;
+        if (sparse) {
+            row = (row < NC) ? clist[row] : 0x3fffffff;
+            // the per-lane positions are only needed again where a tile touches the diagonal (and for the norms):
+            // parked in LDS meanwhile (each lane reads back what it wrote itself, so no barrier is involved)
+            spos[cg * 256 + tid] = row;
+        }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
+        for (int ks = 0; ks < 4; ++ks) {
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (row < L) v = *reinterpret_cast<const uint4*>(S + (size_t)row * SD + ks * 16 + half * 8);
-            sf[cb][ks] = as_bf16x8(v);
+            if (row < L) v = *reinterpret_cast<const uint4*>(S + (size_t)row * SD + ks * 32 + q4 * 8);
+            sf[cg][ks] = as_bf16x8(v);
         }
     }
 
@@ -314,9 +328,20 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
     float stage_l = 0.f;
     // byte offset of this lane's 16 bytes inside a tile: row (wave*4 + ld_sub) of the first 1 KB piece, swizzled chunk
     // (the 16 rows between two pieces do not change row & 7)
-    const uint32_t lane_off = (uint32_t)((wave * 4 + ld_sub) * (SD * 2) + ((ld_pos ^ ((wave * 4 + ld_sub) & 7)) * 16));
+    // (pass 1 works it out again for every tile - six instructions - instead of holding it: with its registers all
+    // taken the compiler otherwise parks it in scratch memory and waits for the reload at the top of every tile)
+    auto lane_offset = [&]() {
+        int t = lane;
+        if (PASS == 1) {   // the lane number afresh (two instructions), so that no register has to hold it meanwhile
+            t = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+            asm volatile("" : "+v"(t));
+        }
+        const int sub = t >> 4, pos = t & 15;
+        return (uint32_t)((wave * 4 + sub) * (SD * 2) + ((pos ^ ((wave * 4 + sub) & 7)) * 16));
+    };
     const char* Xb = reinterpret_cast<const char*>(X);
     auto load_tile = [&](int x0, bf16_t* xsb) {
+        const uint32_t lane_off = lane_offset();
         if (x0 + BX <= L) {          // scalar test: a whole tile inside the tensor needs no clamping
             const uint32_t o = (uint32_t)x0 * (SD * 2) + lane_off;
 #pragma unroll
@@ -351,25 +376,25 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         }
     };
 
-    float m[2] = {-1e30f, -1e30f}, l[2] = {0.f, 0.f};   // pass 1 state per stationary row of this lane
-    float run[2] = {0.f, 0.f};                          // pass 2 state
+    float m[4] = {-1e30f, -1e30f, -1e30f, -1e30f}, l[4] = {0.f, 0.f, 0.f, 0.f};   // pass 1 state per stationary row of this lane
+    float run[4] = {0.f, 0.f, 0.f, 0.f};                                            // pass 2 state
 
     load_tile(x_begin, xs0);
     store_tile(xl0, x_begin);
     if (PASS == 2 && rnorm != nullptr && g == max(strip_begin, (R0 / BX) * BX) / CT && h % group == 0) {
-        // A key row's 128 dims sit in the lane pair (lane, lane ^ 32): this lane holds the 8-dim groups
-        // 2*ks + half.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
-        // partial sums, number p over groups p and p + 8, then a pairwise tree), so both give the same bits
+        // A key row's 128 dims sit in the four lanes of equal c16: lane q4 holds the 8-dim groups q4, 4 + q4, 8 + q4
+        // and 12 + q4.  The sum of squares is taken in the order of the stand-alone norm kernel (k_rnorm: eight
+        // partial sums, number p over the groups p and p + 8, then a pairwise tree), so both give the same bits
         // and the stage call lookm_nearest reproduces the matching of the whole path exactly.
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            double part[4];   // partial sums number 2*j + half, in binary64 as in k_rnorm
+        for (int cg = 0; cg < 4; ++cg) {
+            double part[2];   // partial sums number q4 and 4 + q4, in binary64 as in k_rnorm
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 2; ++j) {
                 double ss = 0.0;
 #pragma unroll
-                for (int rep = 0; rep < 2; ++rep) {
-                    const uint4 v = __builtin_bit_cast(uint4, sf[cb][j + 4 * rep]);
+                for (int rep = 0; rep < 2; ++rep) {      // group 4*j + q4 (step j), then group 8 + 4*j + q4 (step j + 2)
+                    const uint4 v = __builtin_bit_cast(uint4, sf[cg][j + 2 * rep]);
                     const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
@@ -380,22 +405,23 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                 }
                 part[j] = ss;
             }
-            double pair[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) pair[j] = part[j] + __shfl_xor(part[j], 32);
-            const double ss = (pair[0] + pair[1]) + (pair[2] + pair[3]);
-            // the row's position again: from LDS on the sparse path (not held in a register since the fragment loads)
-            const int row = sparse ? spos[cb * 256 + tid] : w0 + cb * 32 + n;
-            if (half == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = inverse_norm(ss);
+            // (p0 + p1) + (p2 + p3) and (p4 + p5) + (p6 + p7), then their sum
+            double lo4 = part[0] + __shfl_xor(part[0], 16), hi4 = part[1] + __shfl_xor(part[1], 16);
+            lo4 += __shfl_xor(lo4, 32);
+            hi4 += __shfl_xor(hi4, 32);
+            const double ss = lo4 + hi4;
+            const int row = stationary_pos(cg);
+            if (q4 == 0 && row < L) rnorm[(size_t)(h / group) * L + row] = inverse_norm(ss);
         }
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the direct-to-LDS loads have landed
     __syncthreads();
 
-    // element offsets of this lane's first four fragments inside its LDS row (swizzled chunks)
-    int frag_off[4];
+    // element offsets of this lane's first two fragments inside its LDS row (swizzled chunks 4*ks + q4); the
+    // chunks of steps 2 and 3 lie 8 chunks after those of steps 0 and 1
+    int frag_off[2];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) frag_off[ks] = ((2 * ks + half) ^ (n & 7)) * 8;
+    for (int ks = 0; ks < 2; ++ks) frag_off[ks] = ((4 * ks + q4) ^ (c16 & 7)) * 8;
 
     // Which tiles need the mask (wave-uniform, so the choice is a scalar branch):
     //   pass 1, keys stream upwards: tiles with x0 + BX - 1 <= w0 hold only keys at or before every query row of
@@ -411,14 +437,37 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         plain_from = max(0, min(n_masked, n_it));
         plain_to = n_it;
     }
-    // fragments of one block of 32 streamed rows (the A operands of its 16 MFMAs), fetched one block ahead
-    bf16x8 a[8];
-    auto fetch = [&](const bf16_t* tile_rows, int rb) {
-        const bf16_t* ap = &tile_rows[(rb * 32 + n) * XROW];
+    // fragments of one block of 32 streamed rows (the A operands of its 32 MFMAs: row 16*rg + c16 of the block,
+    // dims 32*ks + 8*q4 .. +7), fetched one block ahead
+    bf16x8 a[2][4];
+    auto fetch_group = [&](const bf16_t* tile_rows, int rb, int rg) {
+        const bf16_t* ap = &tile_rows[(rb * 32 + 16 * rg + c16) * XROW];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {   // chunk (2*(ks+4) + half) ^ (n & 7) lies 8 chunks after that of ks
-            a[ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
-            a[ks + 4] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
+        for (int ks = 0; ks < 2; ++ks) {
+            a[rg][ks] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks]));
+            a[rg][ks + 2] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[ks] + 64));
+        }
+    };
+    auto fetch = [&](const bf16_t* tile_rows, int rb) {
+        fetch_group(tile_rows, rb, 0);
+        fetch_group(tile_rows, rb, 1);
+    };
+    // pass 1 (its epilogue keeps twice the state of pass 2's and needs registers to work in): the fragments of the
+    // first two MFMA steps before the epilogue, those of the last two - needed after sixteen MFMAs - after it
+    auto fetch_early = [&](const bf16_t* tile_rows, int rb) {
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg) {
+            const bf16_t* ap = &tile_rows[(rb * 32 + 16 * rg + c16) * XROW];
+            a[rg][0] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[0]));
+            a[rg][1] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[1]));
+        }
+    };
+    auto fetch_late = [&](const bf16_t* tile_rows, int rb) {
+#pragma unroll
+        for (int rg = 0; rg < 2; ++rg) {
+            const bf16_t* ap = &tile_rows[(rb * 32 + 16 * rg + c16) * XROW];
+            a[rg][2] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[0] + 64));
+            a[rg][3] = as_bf16x8(*reinterpret_cast<const uint4*>(ap + frag_off[1] + 64));
         }
     };
     if (n_it > 0) fetch(xs0, 0);
@@ -442,11 +491,14 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 
         // End of the tile's LDS reads: wait for the next tile's loads, meet the other waves, and fetch the next
         // tile's first fragments - before the epilogue of this tile's second block, which hides their latency.
-        auto finish_tile = [&]() {
+        // (pass 1 fetches only the first row group here and the second after the epilogue: see below)
+        auto finish_tile = [&](bool all_fragments) {
             if (it + 1 < n_it) store_tile(nxt_l, x0 + BX);
             __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the next tile's direct-to-LDS loads have landed
             __syncthreads();
-            fetch(nxt, 0);   // unconditional: after the last tile this reads an old tile and the values are never used
+            // unconditional: after the last tile this reads an old tile and the values are never used
+            if (all_fragments) fetch(nxt, 0);
+            else fetch_early(nxt, 0);
         };
         if (!skip) {
             // Two blocks of 32 streamed rows; the fragments of block 0 are in `a` already (fetched by the previous
@@ -454,69 +506,90 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
             // block's are fetched into the same registers right away and their LDS latency passes under the
             // epilogue.  The scheduling barriers keep the compiler from undoing the order, and from holding more
             // than one block's values at a time: the kernel has to stay within 168 VGPRs.
-            f32x16 Xc, Yc;
-            // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the block's 16 streamed
-            // rows (four 16-byte LDS reads, straight into the first chain's accumulator registers) in pass 2
+            f32x4 acc[2][4];
+            // the MFMA chains of a block start from zero in pass 1 and from -lse2_i / c of the lane's streamed rows
+            // (two 16-byte LDS reads; every chain's first MFMA takes them as its C operand) in pass 2
             auto multiply = [&](int rb) {
                 if (PASS == 1) {
+                    // step by step over all eight tiles, so that a tile's next MFMA is eight instructions away; the
+                    // fragments of the last step were asked for after the previous epilogue and land meanwhile
+                    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};   // an inline constant of the instruction, no registers
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) Xc[r] = 0.f;
+                    for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+                        for (int cg = 0; cg < 4; ++cg)
+                            acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][0], sf[cg][0], zero, 0, 0, 0);
+#pragma unroll
+                    for (int ks = 1; ks < 4; ++ks)
+#pragma unroll
+                        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+                            for (int cg = 0; cg < 4; ++cg)
+                                acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][ks], sf[cg][ks], acc[rg][cg], 0, 0, 0);
                 } else {
-                    const float* nl = &cur_l[rb * 32 + 4 * half];
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const float4 v = *reinterpret_cast<const float4*>(nl + 8 * g);
-                        Xc[4 * g + 0] = v.x; Xc[4 * g + 1] = v.y; Xc[4 * g + 2] = v.z; Xc[4 * g + 3] = v.w;
+                    for (int rg = 0; rg < 2; ++rg) {
+                        const float4 v = *reinterpret_cast<const float4*>(&cur_l[rb * 32 + 16 * rg + 4 * q4]);
+                        const f32x4 init = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int cg = 0; cg < 4; ++cg)
+                            acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][0], sf[cg][0], init, 0, 0, 0);
                     }
-                }
-                // both chains start from the same values: the second chain's first MFMA takes them from the first
-                // chain's registers (as its C operand) before the first chain overwrites them
-                Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], sf[1][0], Xc, 0, 0, 0);
-                Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], sf[0][0], Xc, 0, 0, 0);
 #pragma unroll
-                for (int ks = 1; ks < 8; ++ks) {
-                    Xc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[0][ks], Xc, 0, 0, 0);
-                    Yc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], sf[1][ks], Yc, 0, 0, 0);
+                    for (int ks = 1; ks < 4; ++ks)
+#pragma unroll
+                        for (int rg = 0; rg < 2; ++rg)
+#pragma unroll
+                            for (int cg = 0; cg < 4; ++cg)
+                                acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][ks], sf[cg][ks], acc[rg][cg], 0, 0, 0);
                 }
             };
             auto epilogue = [&](int rb) {
-                const int xb = x0 + rb * 32 + 4 * half;   // streamed index of entry r: xb + 8*(r/4) + r%4
+                const int xq = x0 + rb * 32 + 4 * q4;   // streamed index of entry i of acc[rg][.]: xq + 16*rg + i
                 if (mask) {      // a scalar branch; both sides leave the prefetched fragments alone
-                    if (PASS == 1) lse_pair_epilogue<true>(Xc, Yc, scale2, xb, w0 + n, w0 + 32 + n, m, l);
-                    else if (sparse) colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, spos[tid], spos[256 + tid], run);
-                    else colsum_pair_epilogue<true>(Xc, Yc, scale2, xb, w0 + n, w0 + 32 + n, run);
+                    const int sP[4] = {stationary_pos(0), stationary_pos(1), stationary_pos(2), stationary_pos(3)};
+                    if (PASS == 1) lse_block_epilogue<true>(acc, scale2, xq, sP, m, l);
+                    else colsum_block_epilogue<true>(acc, scale2, xq, sP, run);
                 } else {
-                    if (PASS == 1) lse_pair_epilogue<false>(Xc, Yc, scale2, xb, 0, 0, m, l);
-                    else colsum_pair_epilogue<false>(Xc, Yc, scale2, xb, 0, 0, run);
+                    const int sP[4] = {0, 0, 0, 0};
+                    if (PASS == 1) lse_block_epilogue<false>(acc, scale2, xq, sP, m, l);
+                    else colsum_block_epilogue<false>(acc, scale2, xq, sP, run);
                 }
             };
+            // The two blocks as a loop: unrolled, neither pass fits into 168 VGPRs.  Pass 1, whose epilogue keeps
+            // twice the state of pass 2's, holds only HALF of the next block's fragments (row group 0) during the
+            // epilogue and asks for the other half after it.
             if (PASS == 1) {
                 multiply(0);
                 __builtin_amdgcn_sched_barrier(0);
-                fetch(cur, 1);
+                fetch_early(cur, 1);
                 __builtin_amdgcn_sched_barrier(0);
                 epilogue(0);
                 __builtin_amdgcn_sched_barrier(0);
+                fetch_late(cur, 1);
+                __builtin_amdgcn_sched_barrier(0);
                 multiply(1);
                 __builtin_amdgcn_sched_barrier(0);
-                finish_tile();
+                finish_tile(false);
                 __builtin_amdgcn_sched_barrier(0);
                 epilogue(1);
+                __builtin_amdgcn_sched_barrier(0);
+                fetch_late(nxt, 0);
+                __builtin_amdgcn_sched_barrier(0);
             } else {
-                // the same schedule as a loop: unrolled, pass 2 does not fit into 168 VGPRs
 #pragma unroll 1
                 for (int rb = 0; rb < BX / 32; ++rb) {
                     multiply(rb);
                     __builtin_amdgcn_sched_barrier(0);
                     if (rb == 0) fetch(cur, 1);
-                    else finish_tile();
+                    else finish_tile(true);
                     __builtin_amdgcn_sched_barrier(0);
                     epilogue(rb);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         } else {
-            finish_tile();
+            finish_tile(true);
         }
     };
     for (int it = 0; it < n_it; it += 2) {
@@ -524,23 +597,34 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
         if (it + 1 < n_it) tile_step(std::integral_constant<int, 1>{}, it + 1);
     }
 
-    // fold the lane pair (lane, lane^32) that shares a stationary row, lower half first, and write the
-    // chunk's partial for rows 0..255 of the strip
+    // fold the four lanes (equal c16) that share a stationary row - the pairs (q4, q4 ^ 1) first, lower lane first,
+    // then the two pairs - and write the chunk's partial for rows 0..255 of the strip
     float* pa = part_a + ((size_t)h * n_chunks_total * nSp + u) * BS;
     float* pb = part_b + ((size_t)h * n_chunks_total * nSp + u) * BS;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int r = wave * 64 + cb * 32 + n;
+    for (int cg = 0; cg < 4; ++cg) {
+        const int r = wave * 64 + cg * 16 + c16;
         if (PASS == 1) {
-            const float mo = __shfl_xor(m[cb], 32), lo = __shfl_xor(l[cb], 32);
-            const float M = fmaxf(m[cb], mo);
-            const float la = half ? lo : l[cb], ma = half ? mo : m[cb];
-            const float lb = half ? l[cb] : lo, mb = half ? m[cb] : mo;
-            const float Ls = la * __builtin_amdgcn_exp2f(ma - M) + lb * __builtin_amdgcn_exp2f(mb - M);
-            if (half == 0) { pa[r] = M; pb[r] = Ls; }
+            float mm = m[cg], ll = l[cg];
+#pragma unroll
+            for (int step = 16; step <= 32; step <<= 1) {
+                const bool upper = (lane & step) != 0;
+                const float mo = __shfl_xor(mm, step), lo = __shfl_xor(ll, step);
+                const float M = fmaxf(mm, mo);
+                const float la = upper ? lo : ll, ma = upper ? mo : mm;   // the lower lane's values first
+                const float lb = upper ? ll : lo, mb = upper ? mm : mo;
+                ll = la * __builtin_amdgcn_exp2f(ma - M) + lb * __builtin_amdgcn_exp2f(mb - M);
+                mm = M;
+            }
+            if (q4 == 0) { pa[r] = mm; pb[r] = ll; }
         } else {
-            const float other = __shfl_xor(run[cb], 32);
-            if (half == 0) pa[r] = half ? other + run[cb] : run[cb] + other;
+            float v = run[cg];
+#pragma unroll
+            for (int step = 16; step <= 32; step <<= 1) {
+                const float other = __shfl_xor(v, step);
+                v = (lane & step) ? other + v : v + other;
+            }
+            if (q4 == 0) pa[r] = v;
         }
     }
 }
