@@ -515,16 +515,16 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
                     // fragments of the last step were asked for after the previous epilogue and land meanwhile
                     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};   // an inline constant of the instruction, no registers
 #pragma unroll
-                    for (int rg = 0; rg < 2; ++rg)
+                    for (int cg = 0; cg < 4; ++cg)
 #pragma unroll
-                        for (int cg = 0; cg < 4; ++cg)
+                        for (int rg = 0; rg < 2; ++rg)
                             acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][0], sf[cg][0], zero, 0, 0, 0);
 #pragma unroll
                     for (int ks = 1; ks < 4; ++ks)
 #pragma unroll
-                        for (int rg = 0; rg < 2; ++rg)
+                        for (int cg = 0; cg < 4; ++cg)
 #pragma unroll
-                            for (int cg = 0; cg < 4; ++cg)
+                            for (int rg = 0; rg < 2; ++rg)
                                 acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][ks], sf[cg][ks], acc[rg][cg], 0, 0, 0);
                 } else {
 #pragma unroll
@@ -538,9 +538,9 @@ k_score_mfma(const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int H, 
 #pragma unroll
                     for (int ks = 1; ks < 4; ++ks)
 #pragma unroll
-                        for (int rg = 0; rg < 2; ++rg)
+                        for (int cg = 0; cg < 4; ++cg)
 #pragma unroll
-                            for (int cg = 0; cg < 4; ++cg)
+                            for (int rg = 0; rg < 2; ++rg)
                                 acc[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg][ks], sf[cg][ks], acc[rg][cg], 0, 0, 0);
                 }
             };
