@@ -268,11 +268,13 @@ def main() -> int:
 
     if args.probe_mfma:
         res = {}
-        for rnd in (False, True):
+        for mode, name in ((0, "32x32x16_constant"), (1, "32x32x16_random"), (2, "16x16x32_random")):
             for wps in (1, 2, 3):
-                res[f"{'random' if rnd else 'constant'}_operands_{wps}_waves_per_simd"] = round(
-                    lookm.lookm_probe_mfma(rnd, wps, iters=2048 * 3 // wps, reps=20), 1)
-        print(json.dumps({"probe": "v_mfma_f32_32x32x16_bf16 from registers, 16 per block in two accumulator chains",
+                res[f"{name}_operands_{wps}_waves_per_simd"] = round(
+                    lookm.lookm_probe_mfma(mode, wps, iters=2048 * 3 // wps, reps=20), 1)
+        print(json.dumps({"probe": "bf16 MFMA from registers, blocks of 64 x 32 x 128 multiply-adds: 16 of "
+                                   "v_mfma_f32_32x32x16_bf16 in two chains, or 32 of v_mfma_f32_16x16x32_bf16 on eight "
+                                   "accumulators",
                           "unit": "TFLOP/s", "datasheet_peak": PEAK_MFMA_BF16 / 1e12, "sustained": res}))
         return 0
 
@@ -414,10 +416,11 @@ def main() -> int:
     # operands that change every instruction, from registers alone (measured after the timed region)
     mfma_sustained = None
     if w.dtype == "bf16":
-        mfma_sustained = round(lookm.lookm_probe_mfma(True, 3, iters=2048, reps=20), 1)
+        mfma_sustained = round(lookm.lookm_probe_mfma(2, 3, iters=2048, reps=20), 1)
         roofline["sustained_mfma_probe"] = {"value": mfma_sustained, "unit": "TFLOP/s",
-                                            "what": "v_mfma_f32_32x32x16_bf16 from registers, random operands, "
-                                                    "3 waves per SIMD (lookm_probe_mfma)"}
+                                            "what": "v_mfma_f32_16x16x32_bf16 (the score kernels' instruction) from "
+                                                    "registers, random operands, 3 waves per SIMD (lookm_probe_mfma)",
+                                            "same_with_32x32x16": round(lookm.lookm_probe_mfma(1, 3, iters=2048, reps=20), 1)}
 
     metric = "prompt KV tokens compressed/sec per layer (12K ctx)"
     if args.reuse_lse:

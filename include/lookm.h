@@ -378,14 +378,16 @@ int lookm_job_profile(const lookm_job* job, int reps, float* kernel_ms_host, voi
 
 /*
  * Measurement aid, no part of the method (for callers that want the realistic ceiling of the MFMA-bound kernels
- * next to the datasheet peak): the rate at which this GPU sustains v_mfma_f32_32x32x16_bf16, the instruction the
- * score and matching kernels are built on, from registers alone - 8 A and 16 B fragments per wave, blocks of 16
- * MFMAs in two accumulator chains, no memory traffic.
- *   random_operands  0: every operand element is 1.0;  1: pseudo-random bf16 values of magnitude [0.25, 4) that differ
- *                    from instruction to instruction, as real queries and keys do (the chip sustains less then)
+ * next to the datasheet peak): the rate at which this GPU sustains the bf16 MFMA instructions the score and matching
+ * kernels are built on, from registers alone - 8 A and 16 B fragments per wave, blocks of 64 x 32 x 128 multiply-adds
+ * as 16 MFMAs of 32x32x16 in two accumulator chains (the matching kernel's block) or as 32 MFMAs of 16x16x32 on eight
+ * accumulators (the score kernels' block), no memory traffic.
+ *   random_operands  0: every operand element is 1.0, 32x32x16;  1: pseudo-random bf16 values of magnitude [0.25, 4)
+ *                    that differ from instruction to instruction, as real queries and keys do (the chip sustains
+ *                    less then), 32x32x16;  2: the same operands through 16x16x32
  *   waves_per_simd   1..3: the grid is (compute units x waves_per_simd) workgroups of 256 threads
- *   iters            1..2^20 blocks of 16 MFMAs per wave and launch;  reps  1..1000 launches, the first half untimed
- *   tflops_host      host, one float: 2*32*32*16 flop per MFMA over the time of the timed launches, in TFLOP/s
+ *   iters            1..2^20 blocks per wave and launch;  reps  1..1000 launches, the first half untimed
+ *   tflops_host      host, one float: 2*64*32*128 flop per block over the time of the timed launches, in TFLOP/s
  *   workspace        device, at least compute units x waves_per_simd x 1024 bytes (1 MiB always suffices), written
  * Like the profile calls it SYNCHRONISES the stream and creates / destroys two HIP events.  Errors: INVALID_ARG
  * for a null pointer or a count outside the ranges above, WORKSPACE for a workspace that is too small, DEVICE.

@@ -1,7 +1,8 @@
-// Measurement aid, no part of the method: the rate the gfx950 matrix cores sustain on the instruction the score
-// and matching kernels are built on (v_mfma_f32_32x32x16_bf16), with everything else taken away.  Every wave
-// keeps 8 A fragments and 16 B fragments in registers and issues blocks of 16 MFMAs in two accumulator chains -
-// the inner block of the score kernels without LDS, memory or epilogue.  With constant operands the chip runs
+// Measurement aid, no part of the method: the rate the gfx950 matrix cores sustain on the instructions the score
+// and matching kernels are built on, with everything else taken away.  Every wave keeps 8 A fragments and 16 B
+// fragments in registers and issues blocks of 64 x 32 x 128 multiply-adds: 16 MFMAs of 32x32x16 in two accumulator
+// chains (the matching kernel's inner block), or 32 MFMAs of 16x16x32 on eight accumulators (the score kernels') -
+// the inner blocks without LDS, memory or epilogue.  With constant operands the chip runs
 // close to its nominal clock; with operands that change from one instruction to the next, as real keys and
 // queries do, it sustains less: that second figure, not the datasheet peak, is what the MFMA-bound kernels of
 // this library can approach, and bench.py prints it beside their rooflines.
@@ -11,6 +12,7 @@ namespace lookm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 pbf16x8;
 typedef __attribute__((ext_vector_type(16))) float pf32x16;
+typedef __attribute__((ext_vector_type(4))) float pf32x4;
 
 __device__ __forceinline__ uint32_t probe_hash(uint32_t x)
 {
@@ -28,6 +30,7 @@ __device__ __forceinline__ uint32_t probe_word(uint32_t key, int random)
     return lo | (hi << 16);
 }
 
+template <int SHAPE>   // 32: v_mfma_f32_32x32x16_bf16, 16: v_mfma_f32_16x16x32_bf16
 __global__ void __launch_bounds__(256, 3)
 k_probe_mfma(int iters, int random, float* __restrict__ sink)
 {
@@ -47,19 +50,39 @@ k_probe_mfma(int iters, int random, float* __restrict__ sink)
             b[cb][ks] = __builtin_bit_cast(pbf16x8, w);
         }
     }
-    pf32x16 X = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    pf32x16 Y = X;
-#pragma unroll 1
-    for (int i = 0; i < iters; ++i) {
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            X = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], b[0][ks], X, 0, 0, 0);
-            Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], b[1][ks], Y, 0, 0, 0);
-        }
-    }
     float s = 0.f;
+    if (SHAPE == 32) {
+        pf32x16 X = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        pf32x16 Y = X;
+#pragma unroll 1
+        for (int i = 0; i < iters; ++i) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) s += X[r] + Y[r];
+            for (int ks = 0; ks < 8; ++ks) {
+                X = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], b[0][ks], X, 0, 0, 0);
+                Y = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], b[1][ks], Y, 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += X[r] + Y[r];
+    } else {
+        // the same registers as two streamed row groups x four steps (a) and four stationary groups x four steps (b)
+        pf32x4 T[2][4];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) T[j >> 2][j & 3] = pf32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+        for (int i = 0; i < iters; ++i) {
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                for (int cg = 0; cg < 4; ++cg)
+#pragma unroll
+                    for (int rg = 0; rg < 2; ++rg)
+                        T[rg][cg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[rg * 4 + ks], b[cg >> 1][(cg & 1) * 4 + ks],
+                                                                           T[rg][cg], 0, 0, 0);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += T[j >> 2][j & 3][0] + T[j >> 2][j & 3][1] + T[j >> 2][j & 3][2] + T[j >> 2][j & 3][3];
+    }
     sink[gid] = s;
 }
 
@@ -69,7 +92,8 @@ extern "C" int lookm_probe_mfma(int random_operands, int waves_per_simd, int ite
                                 void* workspace, size_t workspace_bytes, void* hip_stream)
 {
     if (!tflops_host || !workspace) return LOOKM_ERR_INVALID_ARG;
-    if (waves_per_simd < 1 || waves_per_simd > 3 || iters < 1 || iters > (1 << 20) || reps < 1 || reps > 1000)
+    if (waves_per_simd < 1 || waves_per_simd > 3 || iters < 1 || iters > (1 << 20) || reps < 1 || reps > 1000 ||
+        random_operands < 0 || random_operands > 2)
         return LOOKM_ERR_INVALID_ARG;
     int dev = 0;
     hipDeviceProp_t prop;
@@ -85,8 +109,11 @@ extern "C" int lookm_probe_mfma(int random_operands, int waves_per_simd, int ite
     int rc = LOOKM_OK;
     for (int r = 0; r < reps; ++r) {
         if (r == warm) (void)hipEventRecord(e0, st);
-        hipLaunchKernelGGL(lookm::k_probe_mfma, dim3(grid), dim3(256), 0, st, iters, random_operands ? 1 : 0,
-                           (float*)workspace);
+        if (random_operands == 2)
+            hipLaunchKernelGGL(lookm::k_probe_mfma<16>, dim3(grid), dim3(256), 0, st, iters, 1, (float*)workspace);
+        else
+            hipLaunchKernelGGL(lookm::k_probe_mfma<32>, dim3(grid), dim3(256), 0, st, iters, random_operands,
+                               (float*)workspace);
     }
     (void)hipEventRecord(e1, st);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(st) != hipSuccess) rc = LOOKM_ERR_DEVICE;

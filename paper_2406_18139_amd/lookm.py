@@ -372,15 +372,16 @@ def lookm_decode_attention_noalloc(q, k_cache, v_cache, out: torch.Tensor, S: Op
     return out
 
 
-def lookm_probe_mfma(random_operands: bool, waves_per_simd: int = 3, iters: int = 4096, reps: int = 20,
+def lookm_probe_mfma(random_operands, waves_per_simd: int = 3, iters: int = 4096, reps: int = 20,
                      workspace: Optional[torch.Tensor] = None) -> float:
-    """lookm_probe_mfma: sustained TFLOP/s of v_mfma_f32_32x32x16_bf16 from registers alone (a measurement aid).
-    Synchronises the current stream."""
+    """lookm_probe_mfma: sustained TFLOP/s of the bf16 MFMA from registers alone (a measurement aid).
+    random_operands: 0 / False constant operands, 1 / True random operands (both v_mfma_f32_32x32x16_bf16),
+    2 random operands through v_mfma_f32_16x16x32_bf16.  Synchronises the current stream."""
     if workspace is None:
         workspace = torch.empty((1 << 20) + 256, dtype=torch.uint8, device="cuda")
     wp, wn = _ws_ptr(workspace)
     out = ctypes.c_float(0.0)
-    rc = lib().lookm_probe_mfma(int(bool(random_operands)), int(waves_per_simd), int(iters), int(reps),
+    rc = lib().lookm_probe_mfma(int(random_operands), int(waves_per_simd), int(iters), int(reps),
                                 ctypes.byref(out), wp, wn, _stream())
     if rc != OK:
         raise LookmError(rc, "lookm_probe_mfma")

@@ -207,6 +207,7 @@ def test_probe_rejects_bad_arguments():
     assert call(wps=0) == lookm.ERR_INVALID_ARG and call(wps=4) == lookm.ERR_INVALID_ARG
     assert call(iters=0) == lookm.ERR_INVALID_ARG and call(iters=(1 << 20) + 1) == lookm.ERR_INVALID_ARG
     assert call(reps=0) == lookm.ERR_INVALID_ARG and call(reps=1001) == lookm.ERR_INVALID_ARG
+    assert call(rnd=-1) == lookm.ERR_INVALID_ARG and call(rnd=3) == lookm.ERR_INVALID_ARG
 
 
 def test_binding_refuses_cpu_tensors():
