@@ -122,7 +122,9 @@ size_t lookm_workspace_bytes(int H, int L, int d, int budget, lookm_dtype dt);
  *   k_out, v_out   device, [H, B, d] of dtype dt; row r of head h is the (merged) row of original
  *                  position kept_idx[h, r].  fp32 accumulation, one round-to-nearest-even to bf16.
  *   kept_idx       device, int32 [H, B], strictly ascending original positions.
- *   scores_out     device, float [H, L], the raw A_s of Eq. 4 (no text prior added), or NULL.
+ *   scores_out     device, float [H, L], the raw A_s of Eq. 4 (no text prior added), or NULL.  With NULL (and
+ *                  bf16, d = 128) the second score pass runs only over the keys that compete in the selection -
+ *                  image tokens before the recent window - which is faster; the cache comes out bit for bit the same.
  *   status_out     device, int32 [1]: LOOKM_OK or LOOKM_ERR_BUDGET_BELOW_PROTECTED. Must not be NULL.
  *   workspace      device scratch of at least lookm_workspace_bytes(H, L, d, budget, dt) bytes.
  */
